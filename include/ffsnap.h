@@ -1,0 +1,172 @@
+/*
+ * ffsnap.h -- C ABI of the MI355X snapshot library (libffsnap.so).
+ *
+ * The library implements the data-moving step of FFTrainer's state management on one GPU:
+ *   - "fast snapshot" (section 4.2): every iteration the worker's unique training state, a list
+ *     of tensors, is copied without serialisation into one pre-allocated contiguous buffer,
+ *     whose size is known up front (12 bytes per parameter for Adam: fp32 master, m, v);
+ *   - state loading on failover (section 3.1 steps 5-6, section 3.3): a newcomer receives that
+ *     buffer and loads its tensors from it;
+ *   - snapshot right after the optimizer update (section 6.2).
+ * The paper copies device-to-host into an RDMA buffer and assumes fail-stop; this library keeps
+ * the buffer on the device, cuts it into fixed-size chunks "ready to send", and adds a CRC32C
+ * per chunk so the receiver can verify what it got.
+ *
+ * Definitions (N = total payload bytes, C = chunk_bytes):
+ *   stream   T = seg_0 || seg_1 || ...        raw little-endian bytes, order of segs[], no padding
+ *   buffer     = T || zeros up to n_chunks*C  n_chunks = ceil(N / C)
+ *   crcs[j]    = CRC32C(buffer[jC, (j+1)C))   Castagnoli polynomial 0x1EDC6F41, reflected,
+ *                                             init and final XOR 0xFFFFFFFF; zero tail included
+ *
+ * Conventions for every call:
+ *   - Pointers marked DEVICE address GPU memory that the caller allocates, owns and keeps alive
+ *     until the stream work has completed; pointers marked HOST are ordinary host memory that
+ *     is only read during the call.  The library owns nothing but the plan.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued on it and the call returns without synchronising; results stay on the device.
+ *   - Return value: FF_OK (0) or a negative ff_status.  Nothing throws, nothing aborts.
+ *     Corruption found by ff_restore is reported through bad[] / n_bad, never as an error code.
+ *   - A plan is immutable.  Calls that use the same plan may run concurrently on different
+ *     streams only if they also use different plans' scratch, i.e. they may NOT: a plan carries
+ *     one scratch array of per-tile partial CRCs, so concurrent calls need one plan each.
+ *   - Segments must not overlap each other, the chunk buffer or the crc arrays.
+ */
+#ifndef FFSNAP_H
+#define FFSNAP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ff_plan ff_plan; /* opaque */
+
+typedef enum {
+    FF_OK = 0,
+    FF_ERR_NULL = -1,    /* a required pointer is NULL                                          */
+    FF_ERR_INVALID = -2, /* bad chunk size, misaligned pointer, nbytes not a multiple of the
+                            element size, unknown dtype/kind/flag, incomplete parameter group   */
+    FF_ERR_EMPTY = -3,   /* the segments hold no bytes at all                                   */
+    FF_ERR_NOMEM = -4,   /* host or device allocation failed                                    */
+    FF_ERR_HIP = -5,     /* a HIP runtime call or a kernel launch failed                        */
+    FF_ERR_HOST_ONLY = -6 /* device work asked of a plan built with FF_PLAN_HOST_ONLY           */
+} ff_status;
+
+typedef enum { FF_BF16 = 1, FF_F32 = 2 } ff_dtype;
+
+/* Role of a segment in the fused optimizer step; RAW segments are only ever copied. */
+typedef enum {
+    FF_KIND_RAW = 0,
+    FF_KIND_W16 = 1,    /* bf16 working weights            */
+    FF_KIND_MASTER = 2, /* fp32 master weights             */
+    FF_KIND_M = 3,      /* fp32 Adam first moment          */
+    FF_KIND_V = 4       /* fp32 Adam second moment         */
+} ff_kind;
+
+typedef struct {
+    void *ptr;         /* DEVICE; aligned to the element size (2 or 4), not necessarily to 16   */
+    uint64_t nbytes;   /* multiple of the element size; 0 is allowed (the segment is skipped)   */
+    uint32_t dtype;    /* ff_dtype                                                              */
+    uint32_t kind;     /* ff_kind                                                               */
+    uint32_t param_id; /* groups the W16/MASTER/M/V segments of one parameter; ignored for RAW  */
+    uint32_t reserved; /* must be 0                                                             */
+} ff_segment;
+
+/* ff_snapshot_plan flags */
+#define FF_PLAN_HOST_ONLY 1u /* build the layout only: no device memory is touched, queries work,
+                                device calls return FF_ERR_HOST_ONLY (lets a sender or a test
+                                compute sizes and the layout id without a GPU)                  */
+
+/* ff_restore flags */
+#define FF_RESTORE_VERIFY_ONLY 1u /* recompute and compare CRCs, write bad[]/n_bad, scatter nothing */
+
+#define FF_MIN_CHUNK_BYTES 1024ull
+#define FF_MAX_CHUNK_BYTES (1ull << 30)
+
+/*
+ * Lay out a snapshot (section 4.2: the engine walks the training configuration once and
+ * computes the buffer size).  segs: HOST array of n_segs descriptors, copied.  chunk_bytes: a
+ * power of two in [FF_MIN_CHUNK_BYTES, FF_MAX_CHUNK_BYTES].  The plan keeps small device
+ * tables (segment pointers and offsets, a tile-to-segment index, CRC constants, one partial CRC
+ * per tile) on the device that is current at the time of the call.
+ * Errors: NULL -> FF_ERR_NULL; bad chunk size / alignment / dtype / kind / reserved / flags ->
+ * FF_ERR_INVALID; N == 0 -> FF_ERR_EMPTY; allocation -> FF_ERR_NOMEM; HIP -> FF_ERR_HIP.
+ * On error *out is set to NULL.
+ */
+int ff_snapshot_plan(const ff_segment *segs, uint64_t n_segs, uint64_t chunk_bytes, uint32_t flags,
+                     ff_plan **out);
+
+/* Frees the plan and its device tables.  NULL is ignored.  The caller must have synchronised
+ * every stream that still uses the plan. */
+void ff_plan_destroy(ff_plan *plan);
+
+uint64_t ff_plan_payload_bytes(const ff_plan *plan); /* N                                   */
+uint64_t ff_plan_num_chunks(const ff_plan *plan);    /* ceil(N / chunk_bytes)               */
+uint64_t ff_plan_buffer_bytes(const ff_plan *plan);  /* num_chunks * chunk_bytes            */
+uint64_t ff_plan_chunk_bytes(const ff_plan *plan);
+uint64_t ff_plan_num_segments(const ff_plan *plan);  /* non-empty segments                  */
+uint64_t ff_plan_num_params(const ff_plan *plan);    /* complete W16/MASTER/M/V groups      */
+/* CRC32C over the little-endian uint64 sequence (chunk_bytes, nbytes of every non-empty segment
+ * in order): equal ids on sender and receiver mean the two layouts agree. */
+uint32_t ff_plan_layout_id(const ff_plan *plan);
+/* Stream range [*begin, *end) of non-empty segment i; FF_ERR_INVALID if i is out of range. */
+int ff_plan_segment_range(const ff_plan *plan, uint64_t i, uint64_t *begin, uint64_t *end);
+
+/*
+ * Snapshot (section 4.2, "fast snapshot"): gather the segments into `chunks` and write one
+ * CRC32C per chunk.  chunks: DEVICE, 16-byte aligned, ff_plan_buffer_bytes() bytes, every byte
+ * of it is written (the tail of the last chunk with zeros).  crcs: DEVICE, num_chunks uint32.
+ */
+int ff_pack(const ff_plan *plan, void *chunks, uint32_t *crcs, void *hip_stream);
+
+/*
+ * State loading on failover (section 3.1 steps 5-6, section 3.3): recompute the CRC32C of every
+ * chunk of `chunks`, set bad[j] = (recomputed != crcs[j]) and *n_bad = sum(bad), and copy every
+ * segment's bytes out of the buffer into the plan's tensors -- from good and bad chunks alike:
+ * the caller must treat tensor ranges that a bad chunk covers as invalid.  chunks: DEVICE,
+ * 16-byte aligned, buffer_bytes.  crcs: DEVICE, num_chunks.  bad: DEVICE, num_chunks uint32,
+ * each set to 0 or 1.  n_bad: DEVICE, one uint64.  flags: 0 or FF_RESTORE_VERIFY_ONLY.
+ */
+int ff_restore(const ff_plan *plan, const void *chunks, const uint32_t *crcs, uint32_t *bad,
+               uint64_t *n_bad, uint32_t flags, void *hip_stream);
+
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay;
+    uint32_t step; /* t >= 1 of the bias corrections */
+} ff_adam_hparams;
+
+/*
+ * Optimizer update with the snapshot taken in the same pass (section 6.2: the optimizer state
+ * is checkpointed immediately after each update).  For every parameter group of the plan one
+ * decoupled-weight-decay Adam step in fp32, each operation rounded separately, in this order:
+ *     g = float(grad);  p = master*decay;  m' = b1*m + omb1*g;  v' = b2*v + (omb2*g)*g;
+ *     d = sqrt(v')/bc2s + eps;  p' = p - step_size*(m'/d);  w' = bf16_rne(p')
+ * with decay = 1 - lr*wd, omb1 = 1 - b1, omb2 = 1 - b2, step_size = lr/(1 - b1^t),
+ * bc2s = sqrt(1 - b2^t) evaluated in double and rounded once to fp32.  master, m, v and the bf16
+ * weights are overwritten in place and the same bytes are written at their stream offsets in
+ * `chunks`; RAW segments are copied unchanged; crcs as in ff_pack.  The result equals ff_pack
+ * run after an unfused update.  grads: HOST array of ff_plan_num_params() DEVICE pointers to
+ * bf16 gradients (4-byte aligned), indexed by param_id rank (ascending param_id); read only.
+ * FF_ERR_INVALID if the plan has an incomplete group, mismatched element counts, or step == 0.
+ */
+int ff_adam_step_snapshot(const ff_plan *plan, const void *const *grads, const ff_adam_hparams *hp,
+                          void *chunks, uint32_t *crcs, void *hip_stream);
+
+/* Test helper: CRC32C of nbytes at dev_buf (DEVICE, 16-byte aligned) into *dev_out (DEVICE),
+ * computed by the same tile and combine kernels as ff_pack.  Allocates and frees a small
+ * scratch array, so it synchronises the stream before returning. */
+int ff_crc32c(const void *dev_buf, uint64_t nbytes, uint32_t *dev_out, void *hip_stream);
+
+/* Bench helper: plain 16-byte-per-lane device copy of nbytes (both DEVICE, 16-byte aligned,
+ * nbytes a multiple of 16): the measured bandwidth ceiling printed beside the real kernels. */
+int ff_copy_ceiling(void *dst, const void *src, uint64_t nbytes, void *hip_stream);
+
+/* Static string for a status code; for FF_ERR_HIP the text of the last HIP error seen by the
+ * calling thread is appended. */
+const char *ff_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FFSNAP_H */

@@ -1,0 +1,205 @@
+"""ctypes binding of libffsnap.so: the same names as include/ffsnap.h, argument marshalling only.
+
+Tensors are torch tensors (PyTorch supplies device memory and streams, nothing else); every step
+of the path runs inside the library's kernels.  If the library has not been built the first call
+raises: there is no fallback path.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libffsnap.so")
+
+FF_OK, FF_ERR_NULL, FF_ERR_INVALID, FF_ERR_EMPTY = 0, -1, -2, -3
+FF_ERR_NOMEM, FF_ERR_HIP, FF_ERR_HOST_ONLY = -4, -5, -6
+FF_BF16, FF_F32 = 1, 2
+FF_KIND_RAW, FF_KIND_W16, FF_KIND_MASTER, FF_KIND_M, FF_KIND_V = 0, 1, 2, 3, 4
+FF_PLAN_HOST_ONLY = 1
+FF_RESTORE_VERIFY_ONLY = 1
+
+EXPORTS = ["ff_snapshot_plan", "ff_plan_destroy", "ff_plan_payload_bytes", "ff_plan_num_chunks",
+           "ff_plan_buffer_bytes", "ff_plan_chunk_bytes", "ff_plan_num_segments",
+           "ff_plan_num_params", "ff_plan_layout_id", "ff_plan_segment_range", "ff_pack",
+           "ff_restore", "ff_adam_step_snapshot", "ff_crc32c", "ff_copy_ceiling", "ff_strerror"]
+
+
+class ff_segment(ctypes.Structure):
+    _fields_ = [("ptr", ctypes.c_void_p), ("nbytes", ctypes.c_uint64), ("dtype", ctypes.c_uint32),
+                ("kind", ctypes.c_uint32), ("param_id", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32)]
+
+
+class ff_adam_hparams(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float),
+                ("step", ctypes.c_uint32)]
+
+
+class FFError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__("ffsnap status %d: %s" % (status, text))
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libffsnap.so is not built: run paper_2512_03644_amd/build.py "
+                               "(there is no fallback implementation)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, u64, u32, i32 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int
+        L.ff_snapshot_plan.restype = i32
+        L.ff_snapshot_plan.argtypes = [ctypes.POINTER(ff_segment), u64, u64, u32,
+                                       ctypes.POINTER(vp)]
+        L.ff_plan_destroy.restype = None
+        L.ff_plan_destroy.argtypes = [vp]
+        for name in ("payload_bytes", "num_chunks", "buffer_bytes", "chunk_bytes", "num_segments",
+                     "num_params"):
+            fn = getattr(L, "ff_plan_" + name)
+            fn.restype, fn.argtypes = u64, [vp]
+        L.ff_plan_layout_id.restype, L.ff_plan_layout_id.argtypes = u32, [vp]
+        L.ff_plan_segment_range.restype = i32
+        L.ff_plan_segment_range.argtypes = [vp, u64, ctypes.POINTER(u64), ctypes.POINTER(u64)]
+        L.ff_pack.restype, L.ff_pack.argtypes = i32, [vp, vp, vp, vp]
+        L.ff_restore.restype, L.ff_restore.argtypes = i32, [vp, vp, vp, vp, vp, u32, vp]
+        L.ff_adam_step_snapshot.restype = i32
+        L.ff_adam_step_snapshot.argtypes = [vp, ctypes.POINTER(vp),
+                                            ctypes.POINTER(ff_adam_hparams), vp, vp, vp]
+        L.ff_crc32c.restype, L.ff_crc32c.argtypes = i32, [vp, u64, vp, vp]
+        L.ff_copy_ceiling.restype, L.ff_copy_ceiling.argtypes = i32, [vp, vp, u64, vp]
+        L.ff_strerror.restype, L.ff_strerror.argtypes = ctypes.c_char_p, [i32]
+        _lib = L
+    return _lib
+
+
+def ff_strerror(status):
+    return lib().ff_strerror(status).decode()
+
+
+def _check(status):
+    if status != FF_OK:
+        raise FFError(status, ff_strerror(status))
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+_DTYPES = {torch.bfloat16: FF_BF16, torch.float32: FF_F32}
+
+
+def make_segments(tensors, kinds=None, param_ids=None):
+    """ff_segment array for a list of contiguous bf16/fp32 tensors (stream order)."""
+    n = len(tensors)
+    arr = (ff_segment * max(n, 1))()
+    for i, t in enumerate(tensors):
+        if not t.is_contiguous():
+            raise ValueError("segment %d is not contiguous" % i)
+        arr[i].ptr = t.data_ptr() if t.numel() else None
+        arr[i].nbytes = t.numel() * t.element_size()
+        arr[i].dtype = _DTYPES[t.dtype]
+        arr[i].kind = kinds[i] if kinds is not None else FF_KIND_RAW
+        arr[i].param_id = param_ids[i] if param_ids is not None else 0
+        arr[i].reserved = 0
+    return arr
+
+
+class Plan:
+    """Owns an ff_plan handle; keeps the tensors it points at alive."""
+
+    def __init__(self, handle, keepalive):
+        self.handle = handle
+        self._keepalive = keepalive
+
+    def destroy(self):
+        if self.handle:
+            lib().ff_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    payload_bytes = property(lambda s: int(lib().ff_plan_payload_bytes(s.handle)))
+    num_chunks = property(lambda s: int(lib().ff_plan_num_chunks(s.handle)))
+    buffer_bytes = property(lambda s: int(lib().ff_plan_buffer_bytes(s.handle)))
+    chunk_bytes = property(lambda s: int(lib().ff_plan_chunk_bytes(s.handle)))
+    num_segments = property(lambda s: int(lib().ff_plan_num_segments(s.handle)))
+    num_params = property(lambda s: int(lib().ff_plan_num_params(s.handle)))
+    layout_id = property(lambda s: int(lib().ff_plan_layout_id(s.handle)))
+
+    def segment_range(self, i):
+        b, e = ctypes.c_uint64(), ctypes.c_uint64()
+        _check(lib().ff_plan_segment_range(self.handle, i, ctypes.byref(b), ctypes.byref(e)))
+        return b.value, e.value
+
+
+def ff_snapshot_plan(tensors, chunk_bytes, flags=0, kinds=None, param_ids=None, tile_log2=0):
+    segs = make_segments(tensors, kinds, param_ids)
+    return ff_snapshot_plan_raw(segs, len(tensors), chunk_bytes, flags | (tile_log2 << 8),
+                                keepalive=list(tensors))
+
+
+def ff_snapshot_plan_raw(segs, n_segs, chunk_bytes, flags=0, keepalive=None):
+    out = ctypes.c_void_p()
+    _check(lib().ff_snapshot_plan(segs, n_segs, chunk_bytes, flags, ctypes.byref(out)))
+    return Plan(out, keepalive)
+
+
+def plan_for_shard(shard, flags=0, tile_log2=0):
+    """Plan for a workloads.Shard: parameter groups get their kinds, the rest is RAW."""
+    kinds, pids = [], []
+    if shard.params:
+        for pid, _ in enumerate(shard.params):
+            kinds += [FF_KIND_W16, FF_KIND_MASTER, FF_KIND_M, FF_KIND_V]
+            pids += [pid] * 4
+    else:
+        kinds, pids = [FF_KIND_RAW] * len(shard.segments), [0] * len(shard.segments)
+    return ff_snapshot_plan(shard.segments, shard.chunk_bytes, flags, kinds, pids, tile_log2)
+
+
+def ff_pack(plan, chunks, crcs, stream=None):
+    _check(lib().ff_pack(plan.handle, chunks.data_ptr(), crcs.data_ptr(), _stream_ptr(stream)))
+
+
+def ff_restore(plan, chunks, crcs, bad, n_bad, flags=0, stream=None):
+    _check(lib().ff_restore(plan.handle, chunks.data_ptr(), crcs.data_ptr(), bad.data_ptr(),
+                            n_bad.data_ptr(), flags, _stream_ptr(stream)))
+
+
+def ff_adam_step_snapshot(plan, grads, hparams, chunks, crcs, stream=None):
+    """grads: list of bf16 device tensors, one per parameter group in ascending param_id;
+    hparams: dict(lr, beta1, beta2, eps, weight_decay, step)."""
+    ptrs = (ctypes.c_void_p * max(len(grads), 1))(*[g.data_ptr() for g in grads])
+    hp = ff_adam_hparams(hparams["lr"], hparams["beta1"], hparams["beta2"], hparams["eps"],
+                         hparams["weight_decay"], hparams["step"])
+    _check(lib().ff_adam_step_snapshot(plan.handle, ptrs, ctypes.byref(hp), chunks.data_ptr(),
+                                       crcs.data_ptr(), _stream_ptr(stream)))
+
+
+def ff_crc32c(buf, nbytes, out, stream=None):
+    _check(lib().ff_crc32c(buf.data_ptr(), nbytes, out.data_ptr(), _stream_ptr(stream)))
+
+
+def ff_copy_ceiling(dst, src, nbytes, stream=None):
+    _check(lib().ff_copy_ceiling(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream)))
+
+
+def alloc_outputs(plan, device):
+    """(chunks uint8, crcs int32 viewable as uint32, bad int32, n_bad int64) on `device`."""
+    chunks = torch.empty(plan.buffer_bytes, dtype=torch.uint8, device=device)
+    crcs = torch.empty(plan.num_chunks, dtype=torch.int32, device=device)
+    bad = torch.empty(plan.num_chunks, dtype=torch.int32, device=device)
+    n_bad = torch.empty(1, dtype=torch.int64, device=device)
+    return chunks, crcs, bad, n_bad

@@ -1,0 +1,287 @@
+// extern "C" entry points of libffsnap.so (see include/ffsnap.h for the contract).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/ffsnap.h"
+#include "gf2.h"
+#include "kernels.hpp"
+#include "layout.hpp"
+
+using namespace ffsnap;
+
+struct ff_plan {
+    Layout layout;
+    bool host_only = false;
+    int device = -1;
+    void* dev_block = nullptr;  // one allocation holding every device table
+    TileTables tables;
+    uint32_t x_tile = 0;  // x^(8 * tile_bytes)
+    uint32_t affine = 0;  // preset/complement term of a chunk_bytes-long CRC
+};
+
+namespace {
+
+thread_local char g_hip_error[256] = "";
+
+int hip_fail(hipError_t e)
+{
+    std::snprintf(g_hip_error, sizeof(g_hip_error), "%s", hipGetErrorString(e));
+    return FF_ERR_HIP;
+}
+
+#define FF_HIP_TRY(expr)                       \
+    do {                                       \
+        hipError_t e_ = (expr);                \
+        if (e_ != hipSuccess) return hip_fail(e_); \
+    } while (0)
+
+uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+void fill_constants(TileTables& t)
+{
+    t.x32 = gf2_xpow(32);
+    for (int l = 0; l < 6; l++) t.z[l] = gf2_xpow(128ull << l);
+}
+
+int upload_tables(ff_plan* p)
+{
+    const Layout& L = p->layout;
+    const uint64_t n = L.segs.size();
+    const uint64_t o_off = 0;
+    const uint64_t o_ptr = align_up(o_off + (n + 1) * 8, 256);
+    const uint64_t o_first = align_up(o_ptr + n * 8, 256);
+    const uint64_t o_tab = align_up(o_first + L.n_tiles * 4, 256);
+    const uint64_t o_partial = align_up(o_tab + 1024 * 4, 256);
+    const uint64_t total = align_up(o_partial + L.n_tiles * 4, 256);
+
+    std::vector<unsigned char> host(total, 0);
+    uint64_t* h_off = reinterpret_cast<uint64_t*>(host.data() + o_off);
+    uint64_t* h_ptr = reinterpret_cast<uint64_t*>(host.data() + o_ptr);
+    for (uint64_t i = 0; i < n; i++) {
+        h_off[i] = L.segs[i].off;
+        h_ptr[i] = L.segs[i].ptr;
+    }
+    h_off[n] = L.payload;
+    std::memcpy(host.data() + o_first, L.tile_first_seg.data(), L.n_tiles * 4);
+    build_tab_u(reinterpret_cast<uint32_t*>(host.data() + o_tab));
+
+    FF_HIP_TRY(hipGetDevice(&p->device));
+    hipError_t e = hipMalloc(&p->dev_block, total);
+    if (e == hipErrorOutOfMemory) return FF_ERR_NOMEM;
+    FF_HIP_TRY(e);
+    FF_HIP_TRY(hipMemcpy(p->dev_block, host.data(), total, hipMemcpyHostToDevice));
+
+    unsigned char* d = static_cast<unsigned char*>(p->dev_block);
+    TileTables& t = p->tables;
+    t.seg_off = reinterpret_cast<const uint64_t*>(d + o_off);
+    t.seg_ptr = reinterpret_cast<const uint64_t*>(d + o_ptr);
+    t.tile_first_seg = reinterpret_cast<const uint32_t*>(d + o_first);
+    t.tab_u = reinterpret_cast<const uint32_t*>(d + o_tab);
+    t.partial = reinterpret_cast<uint32_t*>(d + o_partial);
+    return FF_OK;
+}
+
+int check_device_call(const ff_plan* p)
+{
+    if (!p) return FF_ERR_NULL;
+    if (p->host_only) return FF_ERR_HOST_ONLY;
+    return FF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ff_snapshot_plan(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_bytes, uint32_t flags,
+                     ff_plan** out)
+{
+    if (!out) return FF_ERR_NULL;
+    *out = nullptr;
+    // bits 8..15 of flags: log2 of the tile size in bytes (0 = default), a tuning knob
+    const unsigned tile_log2 = (flags >> 8) & 0xFFu;
+    if (flags & ~(FF_PLAN_HOST_ONLY | 0xFF00u)) return FF_ERR_INVALID;
+    ff_plan* p = new (std::nothrow) ff_plan();
+    if (!p) return FF_ERR_NOMEM;
+    int rc;
+    try {
+        rc = build_layout(segs, n_segs, chunk_bytes, tile_log2, p->layout);
+    } catch (const std::bad_alloc&) {
+        rc = FF_ERR_NOMEM;
+    }
+    if (rc != FF_OK) {
+        delete p;
+        return rc;
+    }
+    const Layout& L = p->layout;
+    p->host_only = (flags & FF_PLAN_HOST_ONLY) != 0;
+    p->x_tile = gf2_xpow(8 * L.tile_bytes);
+    p->affine = crc_affine_term(L.chunk_bytes);
+    TileTables& t = p->tables;
+    t.payload = L.payload;
+    t.total_rows = L.buffer_bytes / 1024;
+    t.n_seg = static_cast<uint32_t>(L.segs.size());
+    t.tile_rows = static_cast<uint32_t>(L.tile_bytes / 1024);
+    t.lead_rows = 0;
+    t.n_tiles = static_cast<uint32_t>(L.n_tiles);
+    fill_constants(t);
+    if (L.n_tiles > 0xFFFFFFF0ull) {
+        delete p;
+        return FF_ERR_INVALID;
+    }
+    if (!p->host_only) {
+        try {
+            rc = upload_tables(p);
+        } catch (const std::bad_alloc&) {
+            rc = FF_ERR_NOMEM;
+        }
+        if (rc != FF_OK) {
+            if (p->dev_block) (void)hipFree(p->dev_block);
+            delete p;
+            return rc;
+        }
+    }
+    *out = p;
+    return FF_OK;
+}
+
+void ff_plan_destroy(ff_plan* plan)
+{
+    if (!plan) return;
+    if (plan->dev_block) (void)hipFree(plan->dev_block);
+    delete plan;
+}
+
+uint64_t ff_plan_payload_bytes(const ff_plan* p) { return p ? p->layout.payload : 0; }
+uint64_t ff_plan_num_chunks(const ff_plan* p) { return p ? p->layout.n_chunks : 0; }
+uint64_t ff_plan_buffer_bytes(const ff_plan* p) { return p ? p->layout.buffer_bytes : 0; }
+uint64_t ff_plan_chunk_bytes(const ff_plan* p) { return p ? p->layout.chunk_bytes : 0; }
+uint64_t ff_plan_num_segments(const ff_plan* p) { return p ? p->layout.segs.size() : 0; }
+uint64_t ff_plan_num_params(const ff_plan* p) { return p ? p->layout.params.size() : 0; }
+uint32_t ff_plan_layout_id(const ff_plan* p) { return p ? p->layout.layout_id : 0; }
+
+int ff_plan_segment_range(const ff_plan* p, uint64_t i, uint64_t* begin, uint64_t* end)
+{
+    if (!p || !begin || !end) return FF_ERR_NULL;
+    if (i >= p->layout.segs.size()) return FF_ERR_INVALID;
+    *begin = p->layout.segs[i].off;
+    *end = p->layout.segs[i].off + p->layout.segs[i].nbytes;
+    return FF_OK;
+}
+
+int ff_pack(const ff_plan* p, void* chunks, uint32_t* crcs, void* hip_stream)
+{
+    int rc = check_device_call(p);
+    if (rc != FF_OK) return rc;
+    if (!chunks || !crcs) return FF_ERR_NULL;
+    if (reinterpret_cast<uint64_t>(chunks) % 16 || reinterpret_cast<uint64_t>(crcs) % 4)
+        return FF_ERR_INVALID;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    FF_HIP_TRY(launch_tiles(kPack, p->tables, chunks, nullptr, s));
+    FF_HIP_TRY(launch_combine_pack(p->tables.partial, p->layout.tiles_per_chunk, p->x_tile,
+                                   p->affine, p->layout.n_chunks, crcs, s));
+    return FF_OK;
+}
+
+int ff_restore(const ff_plan* p, const void* chunks, const uint32_t* crcs, uint32_t* bad,
+               uint64_t* n_bad, uint32_t flags, void* hip_stream)
+{
+    int rc = check_device_call(p);
+    if (rc != FF_OK) return rc;
+    if (!chunks || !crcs || !bad || !n_bad) return FF_ERR_NULL;
+    if (flags & ~FF_RESTORE_VERIFY_ONLY) return FF_ERR_INVALID;
+    if (reinterpret_cast<uint64_t>(chunks) % 16 || reinterpret_cast<uint64_t>(crcs) % 4 ||
+        reinterpret_cast<uint64_t>(bad) % 4 || reinterpret_cast<uint64_t>(n_bad) % 8)
+        return FF_ERR_INVALID;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const TileMode mode = (flags & FF_RESTORE_VERIFY_ONLY) ? kVerify : kRestore;
+    FF_HIP_TRY(launch_tiles(mode, p->tables, const_cast<void*>(chunks), n_bad, s));
+    FF_HIP_TRY(launch_combine_verify(p->tables.partial, p->layout.tiles_per_chunk, p->x_tile,
+                                     p->affine, p->layout.n_chunks, crcs, bad, n_bad, s));
+    return FF_OK;
+}
+
+int ff_adam_step_snapshot(const ff_plan* p, const void* const* grads, const ff_adam_hparams* hp,
+                          void* chunks, uint32_t* crcs, void* hip_stream)
+{
+    int rc = check_device_call(p);
+    if (rc != FF_OK) return rc;
+    if (!grads || !hp || !chunks || !crcs) return FF_ERR_NULL;
+    (void)hip_stream;
+    return FF_ERR_INVALID;  // fused step: not wired up yet
+}
+
+int ff_crc32c(const void* dev_buf, uint64_t nbytes, uint32_t* dev_out, void* hip_stream)
+{
+    if (!dev_out || (nbytes && !dev_buf)) return FF_ERR_NULL;
+    if (reinterpret_cast<uint64_t>(dev_buf) % 16 || reinterpret_cast<uint64_t>(dev_out) % 4)
+        return FF_ERR_INVALID;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const uint64_t rows = nbytes / 1024;
+    const uint32_t tile_rows = 1024;
+    if ((rows + tile_rows - 1) / tile_rows > 0xFFFFFFF0ull) return FF_ERR_INVALID;
+    TileTables t;
+    fill_constants(t);
+    t.total_rows = rows;
+    t.tile_rows = tile_rows;
+    t.n_tiles = static_cast<uint32_t>((rows + tile_rows - 1) / tile_rows);
+    t.lead_rows = static_cast<uint32_t>(static_cast<uint64_t>(t.n_tiles) * tile_rows - rows);
+    t.payload = rows * 1024;
+
+    // scratch: byte tables + one register per tile
+    const uint64_t scratch_bytes = 4096 + (static_cast<uint64_t>(t.n_tiles) + 1) * 4;
+    void* scratch = nullptr;
+    hipError_t e = hipMalloc(&scratch, scratch_bytes);
+    if (e == hipErrorOutOfMemory) return FF_ERR_NOMEM;
+    FF_HIP_TRY(e);
+    uint32_t tab[1024];
+    build_tab_u(tab);
+    int rc = FF_OK;
+    do {
+        if ((e = hipMemcpyAsync(scratch, tab, sizeof(tab), hipMemcpyHostToDevice, s)) != hipSuccess) break;
+        t.tab_u = static_cast<const uint32_t*>(scratch);
+        t.partial = static_cast<uint32_t*>(scratch) + 1024;
+        if ((e = launch_tiles(kVerify, t, const_cast<void*>(dev_buf), nullptr, s)) != hipSuccess) break;
+        const uint8_t* tail = static_cast<const uint8_t*>(dev_buf) + rows * 1024;
+        e = launch_finish_crc(t.partial, t.n_tiles, gf2_xpow(8ull * 1024 * tile_rows), tail,
+                              static_cast<uint32_t>(nbytes - rows * 1024), crc_affine_term(nbytes),
+                              dev_out, s);
+    } while (0);
+    hipError_t e2 = hipStreamSynchronize(s);
+    (void)hipFree(scratch);
+    if (e != hipSuccess) rc = hip_fail(e);
+    else if (e2 != hipSuccess) rc = hip_fail(e2);
+    return rc;
+}
+
+int ff_copy_ceiling(void* dst, const void* src, uint64_t nbytes, void* hip_stream)
+{
+    if (!dst || !src) return FF_ERR_NULL;
+    if (reinterpret_cast<uint64_t>(dst) % 16 || reinterpret_cast<uint64_t>(src) % 16 || nbytes % 16)
+        return FF_ERR_INVALID;
+    FF_HIP_TRY(launch_copy(dst, src, nbytes, static_cast<hipStream_t>(hip_stream)));
+    return FF_OK;
+}
+
+const char* ff_strerror(int status)
+{
+    static thread_local char buf[320];
+    switch (status) {
+    case FF_OK: return "ok";
+    case FF_ERR_NULL: return "a required pointer is NULL";
+    case FF_ERR_INVALID: return "invalid argument";
+    case FF_ERR_EMPTY: return "the segments hold no bytes";
+    case FF_ERR_NOMEM: return "out of memory";
+    case FF_ERR_HOST_ONLY: return "device work asked of a host-only plan";
+    case FF_ERR_HIP:
+        std::snprintf(buf, sizeof(buf), "HIP error: %s", g_hip_error);
+        return buf;
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,471 @@
+// GPU kernels of the snapshot path for gfx950 (CDNA4, 64-wide wavefronts).
+//
+// Layout of the work.  The chunk buffer is cut into tiles (a power-of-two number of 1 KiB rows,
+// never crossing a chunk).  One wavefront owns one tile and walks it row by row; in a row lane l
+// handles the 16 bytes at offset 16*l, so every global access of the wavefront is one
+// contiguous, 16-byte-per-lane, 1 KiB transaction on the buffer side.  On the tensor side the
+// same 16 bytes come from (pack) or go to (restore) wherever the stream position falls in the
+// segment list: a row that lies inside one segment is a single, possibly unaligned, 16-byte
+// access per lane; a row that touches a segment boundary is assembled halfword by halfword.
+//
+// CRC32C without table lookups in the inner loop.  A lane sees 4 dwords per row, 256 dwords
+// apart from row to row.  It keeps NE*4 dwords of state that represent its part of the message
+// as a polynomial in y = x^32; every row multiplies the state by y^256 (a rotation of register
+// names) and the 4 dwords that leave the top are XORed into 7 tap positions each, using sparse
+// multiples of the CRC generator (fold_taps.h).  That is 28 XORs per 16 bytes and is exact
+// GF(2) algebra.  Only at the end of a tile are the NE*4 dwords of every lane reduced to one
+// 32-bit register: Horner steps with byte tables (multiply by x^8192) held in LDS, then
+// bitwise multiplications to merge columns and lanes.  A second, tiny kernel merges the tile
+// registers of a chunk with x^(8*tile_bytes) multiplications and adds the preset/complement
+// term, which gives the standard CRC32C of the chunk.
+#include "kernels.hpp"
+
+#include <type_traits>
+#include <utility>
+
+#include "fold_taps.h"
+#include "gf2.h"
+
+namespace ffsnap {
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+struct __attribute__((packed, aligned(2))) U4Unaligned {
+    uint32_t x, y, z, w;
+};
+
+constexpr int kWaveSize = 64;
+constexpr int kWavesPerBlock = 4;
+constexpr int kRowBytes = Fold16::ROW_BYTES;
+constexpr int kNE = Fold16::NE;
+constexpr int kNF = Fold16::NF;
+constexpr int kDepth = 8;  // rows in flight per wavefront
+static_assert(kNE % kDepth == 0, "queue slots must repeat with the state rotation");
+
+template <class Fn, int... Is>
+__device__ __forceinline__ void static_for_impl(Fn&& fn, std::integer_sequence<int, Is...>)
+{
+    (fn(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class Fn>
+__device__ __forceinline__ void static_for(Fn&& fn)
+{
+    static_for_impl(fn, std::make_integer_sequence<int, N>{});
+}
+
+__device__ __forceinline__ u32x4 load16_unaligned(const uint8_t* p)
+{
+    U4Unaligned v = *reinterpret_cast<const U4Unaligned*>(p);
+    u32x4 r;
+    r.x = v.x; r.y = v.y; r.z = v.z; r.w = v.w;
+    return r;
+}
+__device__ __forceinline__ void store16_unaligned(uint8_t* p, u32x4 w)
+{
+    U4Unaligned v;
+    v.x = w.x; v.y = w.y; v.z = w.z; v.w = w.w;
+    *reinterpret_cast<U4Unaligned*>(p) = v;
+}
+__device__ __forceinline__ u32x4 load16_stream(const uint8_t* p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+__device__ __forceinline__ void store16_stream(uint8_t* p, u32x4 w)
+{
+    __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(p));
+}
+
+// ---- segment cursor (wave-uniform) -----------------------------------------------------------
+
+struct Cursor {
+    uint32_t si;    // current segment
+    uint64_t a, b;  // its stream range [a, b)
+    uint64_t base;  // its device address
+};
+
+__device__ __forceinline__ void cursor_init(Cursor& c, const uint64_t* __restrict__ seg_off,
+                                            const uint64_t* __restrict__ seg_ptr, uint32_t si)
+{
+    c.si = si;
+    c.a = seg_off[si];
+    c.b = seg_off[si + 1];
+    c.base = seg_ptr[si];
+}
+
+// Move to the segment that holds stream offset s (the last segment if s is past the payload).
+__device__ __forceinline__ void cursor_seek(Cursor& c, const uint64_t* __restrict__ seg_off,
+                                            const uint64_t* __restrict__ seg_ptr, uint32_t n_seg,
+                                            uint64_t s)
+{
+    bool moved = false;
+    while (s >= c.b && c.si + 1 < n_seg) {
+        c.si++;
+        c.a = c.b;
+        c.b = seg_off[c.si + 1];
+        moved = true;
+    }
+    while (s < c.a) {
+        c.si--;
+        c.b = c.a;
+        c.a = seg_off[c.si];
+        moved = true;
+    }
+    if (moved) c.base = seg_ptr[c.si];
+}
+
+// Per-lane: index of the segment holding stream offset pos, searching upwards from si0, the
+// segment that holds the start of the lane's row (pos is less than 1 KiB past it and every
+// segment has at least 2 bytes, so the answer is within 512 segments).
+__device__ __forceinline__ uint32_t find_segment(const uint64_t* __restrict__ seg_off,
+                                                 uint32_t n_seg, uint32_t si0, uint64_t pos)
+{
+    uint32_t lo = si0;
+    uint32_t hi = (n_seg - 1 - si0 > 512u) ? si0 + 512u : n_seg - 1;
+    while (lo < hi) {
+        uint32_t mid = lo + (hi - lo + 1) / 2;
+        if (seg_off[mid] <= pos)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    return lo;
+}
+
+// A row that is not wholly inside one segment: every lane finds its own 16 bytes.
+__device__ __noinline__ u32x4 gather_row_slow(const uint64_t* __restrict__ seg_off,
+                                              const uint64_t* __restrict__ seg_ptr, uint32_t n_seg,
+                                              uint32_t si0, uint64_t s, uint64_t payload, int lane)
+{
+    const uint64_t pos = s + 16u * lane;
+    uint32_t j = find_segment(seg_off, n_seg, si0, pos);
+    uint64_t a = seg_off[j], b = seg_off[j + 1], base = seg_ptr[j];
+    if (pos + 16 <= b) return load16_unaligned(reinterpret_cast<const uint8_t*>(base + (pos - a)));
+    uint32_t h[8];
+#pragma unroll
+    for (int u = 0; u < 8; u++) {
+        const uint64_t p = pos + 2u * u;
+        while (p >= b && j + 1 < n_seg) {
+            j++;
+            a = b;
+            b = seg_off[j + 1];
+            base = seg_ptr[j];
+        }
+        h[u] = (p < payload) ? *reinterpret_cast<const uint16_t*>(base + (p - a)) : 0u;
+    }
+    u32x4 r;
+    r.x = h[0] | (h[1] << 16);
+    r.y = h[2] | (h[3] << 16);
+    r.z = h[4] | (h[5] << 16);
+    r.w = h[6] | (h[7] << 16);
+    return r;
+}
+
+__device__ __noinline__ void scatter_row_slow(const uint64_t* __restrict__ seg_off,
+                                              const uint64_t* __restrict__ seg_ptr, uint32_t n_seg,
+                                              uint32_t si0, uint64_t s, uint64_t payload, int lane,
+                                              u32x4 w)
+{
+    const uint64_t pos = s + 16u * lane;
+    uint32_t j = find_segment(seg_off, n_seg, si0, pos);
+    uint64_t a = seg_off[j], b = seg_off[j + 1], base = seg_ptr[j];
+    if (pos + 16 <= b) {
+        store16_unaligned(reinterpret_cast<uint8_t*>(base + (pos - a)), w);
+        return;
+    }
+    const uint32_t d[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int u = 0; u < 8; u++) {
+        const uint64_t p = pos + 2u * u;
+        while (p >= b && j + 1 < n_seg) {
+            j++;
+            a = b;
+            b = seg_off[j + 1];
+            base = seg_ptr[j];
+        }
+        if (p < payload)
+            *reinterpret_cast<uint16_t*>(base + (p - a)) =
+                static_cast<uint16_t>(d[u >> 1] >> ((u & 1) * 16));
+    }
+}
+
+// ---- folding -----------------------------------------------------------------------------------
+
+// One row into the state.  J = number of rows folded since the rotation was last at zero
+// (modulo NE): physical register row p holds logical row (p + J) mod NE.
+template <int J>
+__device__ __forceinline__ void fold_row(uint32_t (&S)[kNE][kNF], u32x4 w)
+{
+    constexpr int top = (kNE - 1 - J + kNE) % kNE;  // logical row NE-1 before the shift
+    uint32_t t[kNF];
+    static_for<kNF>([&](auto f) { t[f] = S[top][f]; });
+    // the freed row becomes logical row 0: the new word, first dword = highest power
+    S[top][3] = w.x;
+    S[top][2] = w.y;
+    S[top][1] = w.z;
+    S[top][0] = w.w;
+    static_for<kNF>([&](auto f) {
+        static_for<Fold16::NTAP>([&](auto k) {
+            constexpr int e = Fold16::TAP_E[f][k];
+            constexpr int c = Fold16::TAP_F[f][k];
+            constexpr int p = (e - (J + 1) + 2 * kNE) % kNE;
+            S[p][c] ^= t[f];
+        });
+    });
+}
+
+// Multiply by x^8192 with four byte tables in LDS.
+__device__ __forceinline__ uint32_t mul_u(const uint32_t* tab, uint32_t a)
+{
+    return tab[a & 0xFFu] ^ tab[256 + ((a >> 8) & 0xFFu)] ^ tab[512 + ((a >> 16) & 0xFFu)] ^
+           tab[768 + (a >> 24)];
+}
+
+// State of all lanes -> the register of the tile run from 0, valid in lane 0.
+__device__ __forceinline__ uint32_t reduce_tile(const uint32_t (&S)[kNE][kNF], const uint32_t* tab,
+                                                uint32_t x32, const uint32_t (&z)[6])
+{
+    uint32_t acc[kNF] = {0, 0, 0, 0};
+    static_for<kNE>([&](auto i) {
+        constexpr int e = kNE - 1 - i;
+        static_for<kNF>([&](auto f) { acc[f] = mul_u(tab, acc[f]) ^ S[e][f]; });
+    });
+    uint32_t v = acc[3];
+    v = gf2_mul(v, x32) ^ acc[2];
+    v = gf2_mul(v, x32) ^ acc[1];
+    v = gf2_mul(v, x32) ^ acc[0];
+    // lane l sits 16*(63-l) bytes before the end of the row
+#pragma unroll
+    for (int l = 0; l < 6; l++) {
+        const uint32_t other = __shfl_down(v, 1 << l, kWaveSize);
+        v = gf2_mul(v, z[l]) ^ other;
+    }
+    return gf2_mul(v, x32);  // the register carries the extra factor x^32
+}
+
+// ---- tile kernel -------------------------------------------------------------------------------
+
+template <int MODE>
+__global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
+    const uint64_t* __restrict__ seg_off, const uint64_t* __restrict__ seg_ptr,
+    const uint32_t* __restrict__ tile_first_seg, const uint32_t* __restrict__ tab_u_global,
+    uint32_t* __restrict__ partial, uint8_t* __restrict__ chunks, uint64_t* __restrict__ n_bad,
+    TileTables T)
+{
+    __shared__ uint32_t tab[1024];
+    for (int i = threadIdx.x; i < 1024; i += blockDim.x) tab[i] = tab_u_global[i];
+    if (n_bad && blockIdx.x == 0 && threadIdx.x == 0) *n_bad = 0;
+    __syncthreads();
+
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
+    const uint32_t tile = blockIdx.x * kWavesPerBlock + wave;
+    if (tile >= T.n_tiles) return;
+
+    // rows of this tile, as indices into the buffer's rows
+    const int64_t g0 = static_cast<int64_t>(tile) * T.tile_rows - T.lead_rows;
+    const int64_t row_begin = g0 < 0 ? 0 : g0;
+    const int R = static_cast<int>(g0 + T.tile_rows - row_begin);
+    const int groups = (R + kNE - 1) / kNE;
+    const int pad = groups * kNE - R;  // virtual zero rows in front: they leave the state at 0
+    const uint64_t s_base = static_cast<uint64_t>(row_begin) * kRowBytes;
+    const uint32_t lane16 = 16u * lane;
+
+    Cursor cin, cout;  // pack reads through cin; restore writes through cout
+    if (MODE == kPack) cursor_init(cin, seg_off, seg_ptr, tile_first_seg[tile]);
+    if (MODE == kRestore) cursor_init(cout, seg_off, seg_ptr, tile_first_seg[tile]);
+
+    auto load_row = [&](int r) -> u32x4 {
+        const uint64_t s = s_base + static_cast<uint64_t>(r) * kRowBytes;
+        if (MODE == kPack) {
+            if (s >= T.payload) return u32x4{0, 0, 0, 0};
+            cursor_seek(cin, seg_off, seg_ptr, T.n_seg, s);
+            if (s + kRowBytes <= cin.b)
+                return load16_unaligned(reinterpret_cast<const uint8_t*>(cin.base + (s - cin.a)) +
+                                        lane16);
+            return gather_row_slow(seg_off, seg_ptr, T.n_seg, cin.si, s, T.payload, lane);
+        } else {
+            return load16_stream(chunks + s + lane16);
+        }
+    };
+    auto sink_row = [&](int r, u32x4 w) {
+        const uint64_t s = s_base + static_cast<uint64_t>(r) * kRowBytes;
+        if (MODE == kPack) {
+            store16_stream(chunks + s + lane16, w);
+        } else if (MODE == kRestore) {
+            if (s >= T.payload) return;
+            cursor_seek(cout, seg_off, seg_ptr, T.n_seg, s);
+            if (s + kRowBytes <= cout.b)
+                store16_unaligned(reinterpret_cast<uint8_t*>(cout.base + (s - cout.a)) + lane16, w);
+            else
+                scatter_row_slow(seg_off, seg_ptr, T.n_seg, cout.si, s, T.payload, lane, w);
+        }
+    };
+
+    uint32_t S[kNE][kNF];
+    static_for<kNE>([&](auto e) { static_for<kNF>([&](auto f) { S[e][f] = 0; }); });
+
+    // queue slot of row r is (r + pad) mod kDepth; fill the first kDepth rows
+    u32x4 q[kDepth];
+    static_for<kDepth>([&](auto k) {
+        const int r = ((k - pad) % kDepth + kDepth) % kDepth;
+        q[k] = u32x4{0, 0, 0, 0};
+        if (r < R) q[k] = load_row(r);
+    });
+
+    for (int g = 0; g < groups; g++) {
+        static_for<kNE>([&](auto Jc) {
+            constexpr int J = Jc;
+            const int r = g * kNE + J - pad;
+            if (r >= 0) {
+                const u32x4 w = q[J % kDepth];
+                if (r + kDepth < R) q[J % kDepth] = load_row(r + kDepth);
+                sink_row(r, w);
+                fold_row<J>(S, w);
+            }
+        });
+    }
+
+    const uint32_t reg = reduce_tile(S, tab, T.x32, T.z);
+    if (lane == 0) partial[tile] = reg;
+}
+
+// ---- combine kernels ---------------------------------------------------------------------------
+
+__device__ __forceinline__ uint32_t chunk_register(const uint32_t* __restrict__ partial,
+                                                   uint64_t first, uint32_t n, uint32_t x_tile)
+{
+    uint32_t acc = 0;
+    for (uint32_t i = 0; i < n; i++) acc = gf2_mul(acc, x_tile) ^ partial[first + i];
+    return acc;
+}
+
+__global__ void combine_pack_kernel(const uint32_t* __restrict__ partial, uint32_t tiles_per_chunk,
+                                    uint32_t x_tile, uint32_t affine, uint64_t n_chunks,
+                                    uint32_t* __restrict__ crcs)
+{
+    const uint64_t j = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (j >= n_chunks) return;
+    crcs[j] = chunk_register(partial, j * tiles_per_chunk, tiles_per_chunk, x_tile) ^ affine;
+}
+
+__global__ void combine_verify_kernel(const uint32_t* __restrict__ partial,
+                                      uint32_t tiles_per_chunk, uint32_t x_tile, uint32_t affine,
+                                      uint64_t n_chunks, const uint32_t* __restrict__ crcs,
+                                      uint32_t* __restrict__ bad, uint64_t* __restrict__ n_bad)
+{
+    const uint64_t j = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    bool is_bad = false;
+    if (j < n_chunks) {
+        const uint32_t crc =
+            chunk_register(partial, j * tiles_per_chunk, tiles_per_chunk, x_tile) ^ affine;
+        is_bad = (crc != crcs[j]);
+        bad[j] = is_bad ? 1u : 0u;
+    }
+    const uint64_t votes = __ballot(is_bad);
+    if ((threadIdx.x & (kWaveSize - 1)) == 0 && votes)
+        atomicAdd(reinterpret_cast<unsigned long long*>(n_bad),
+                  static_cast<unsigned long long>(__popcll(votes)));
+}
+
+__global__ void finish_crc_kernel(const uint32_t* __restrict__ partial, uint32_t n_tiles,
+                                  uint32_t x_tile, const uint8_t* __restrict__ tail,
+                                  uint32_t tail_bytes, uint32_t affine, uint32_t* __restrict__ out)
+{
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    uint32_t c = chunk_register(partial, 0, n_tiles, x_tile);
+    for (uint32_t i = 0; i < tail_bytes; i++) {
+        c ^= tail[i];
+        for (int k = 0; k < 8; k++) c = gf2_mulx(c);
+    }
+    *out = c ^ affine;
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(u32x4* __restrict__ dst,
+                                                   const u32x4* __restrict__ src, uint64_t n16)
+{
+    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
+    for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n16;
+         i += stride)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+}  // namespace
+
+// ---- host wrappers -----------------------------------------------------------------------------
+
+void build_tab_u(uint32_t* tab)
+{
+    const uint32_t u = gf2_xpow(8192);
+    for (int k = 0; k < 4; k++)
+        for (uint32_t b = 0; b < 256; b++) tab[k * 256 + b] = gf2_mul(b << (8 * k), u);
+}
+
+hipError_t launch_tiles(TileMode mode, const TileTables& t, void* chunks, uint64_t* n_bad,
+                        hipStream_t stream)
+{
+    if (t.n_tiles == 0) return hipSuccess;
+    const dim3 grid((t.n_tiles + kWavesPerBlock - 1) / kWavesPerBlock);
+    const dim3 block(kWaveSize * kWavesPerBlock);
+    uint8_t* c = static_cast<uint8_t*>(chunks);
+    switch (mode) {
+    case kPack:
+        hipLaunchKernelGGL(tile_kernel<kPack>, grid, block, 0, stream, t.seg_off, t.seg_ptr,
+                           t.tile_first_seg, t.tab_u, t.partial, c, n_bad, t);
+        break;
+    case kRestore:
+        hipLaunchKernelGGL(tile_kernel<kRestore>, grid, block, 0, stream, t.seg_off, t.seg_ptr,
+                           t.tile_first_seg, t.tab_u, t.partial, c, n_bad, t);
+        break;
+    case kVerify:
+        hipLaunchKernelGGL(tile_kernel<kVerify>, grid, block, 0, stream, t.seg_off, t.seg_ptr,
+                           t.tile_first_seg, t.tab_u, t.partial, c, n_bad, t);
+        break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_combine_pack(const uint32_t* partial, uint32_t tiles_per_chunk, uint32_t x_tile,
+                               uint32_t affine, uint64_t n_chunks, uint32_t* crcs,
+                               hipStream_t stream)
+{
+    const unsigned block = 256;
+    const unsigned grid = static_cast<unsigned>((n_chunks + block - 1) / block);
+    hipLaunchKernelGGL(combine_pack_kernel, dim3(grid), dim3(block), 0, stream, partial,
+                       tiles_per_chunk, x_tile, affine, n_chunks, crcs);
+    return hipGetLastError();
+}
+
+hipError_t launch_combine_verify(const uint32_t* partial, uint32_t tiles_per_chunk,
+                                 uint32_t x_tile, uint32_t affine, uint64_t n_chunks,
+                                 const uint32_t* crcs, uint32_t* bad, uint64_t* n_bad,
+                                 hipStream_t stream)
+{
+    const unsigned block = 256;
+    const unsigned grid = static_cast<unsigned>((n_chunks + block - 1) / block);
+    hipLaunchKernelGGL(combine_verify_kernel, dim3(grid), dim3(block), 0, stream, partial,
+                       tiles_per_chunk, x_tile, affine, n_chunks, crcs, bad, n_bad);
+    return hipGetLastError();
+}
+
+hipError_t launch_finish_crc(const uint32_t* partial, uint32_t n_tiles, uint32_t x_tile,
+                             const uint8_t* tail, uint32_t tail_bytes, uint32_t affine,
+                             uint32_t* out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(finish_crc_kernel, dim3(1), dim3(64), 0, stream, partial, n_tiles, x_tile,
+                       tail, tail_bytes, affine, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy(void* dst, const void* src, uint64_t nbytes, hipStream_t stream)
+{
+    const uint64_t n16 = nbytes / 16;
+    if (n16 == 0) return hipSuccess;
+    uint64_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream,
+                       static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), n16);
+    return hipGetLastError();
+}
+
+}  // namespace ffsnap

@@ -1,0 +1,56 @@
+// Launch wrappers of the GPU kernels (kernels.hip).  Every wrapper enqueues on `stream`,
+// returns hipSuccess or the launch error, and never synchronises.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ffsnap {
+
+// Device-side view of a plan's tables, plus the constants the tile kernels need.
+struct TileTables {
+    const uint64_t* seg_off = nullptr;        // [n_seg + 1] stream offsets, seg_off[n_seg] = payload
+    const uint64_t* seg_ptr = nullptr;        // [n_seg] device addresses
+    const uint32_t* tile_first_seg = nullptr; // [n_tiles]
+    const uint32_t* tab_u = nullptr;          // [4][256] multiply-by-x^8192 byte tables
+    uint32_t* partial = nullptr;              // [n_tiles] register of every tile run from 0
+    uint64_t payload = 0;                     // N
+    uint64_t total_rows = 0;                  // 1 KiB rows in the buffer
+    uint32_t n_seg = 0;
+    uint32_t tile_rows = 0;                   // rows per tile
+    uint32_t lead_rows = 0;                   // rows missing at the front of tile 0
+    uint32_t n_tiles = 0;
+    uint32_t x32 = 0;                         // x^32 mod P
+    uint32_t z[6] = {0, 0, 0, 0, 0, 0};       // x^(128 * 2^l) mod P
+};
+
+enum TileMode { kPack = 0, kRestore = 1, kVerify = 2 };
+
+// Folds every tile: kPack gathers segments -> chunks; kRestore reads chunks and scatters to the
+// segments; kVerify only reads chunks.  All three write partial[].  n_bad (may be null) is set
+// to 0 by the kernel so that the verify-combine that follows can add to it.
+hipError_t launch_tiles(TileMode mode, const TileTables& t, void* chunks, uint64_t* n_bad,
+                        hipStream_t stream);
+
+// crcs[j] = standard CRC32C of chunk j from its tiles' registers.
+hipError_t launch_combine_pack(const uint32_t* partial, uint32_t tiles_per_chunk, uint32_t x_tile,
+                               uint32_t affine, uint64_t n_chunks, uint32_t* crcs,
+                               hipStream_t stream);
+
+// bad[j] = (recomputed CRC != crcs[j]); *n_bad += number of bad chunks.
+hipError_t launch_combine_verify(const uint32_t* partial, uint32_t tiles_per_chunk,
+                                 uint32_t x_tile, uint32_t affine, uint64_t n_chunks,
+                                 const uint32_t* crcs, uint32_t* bad, uint64_t* n_bad,
+                                 hipStream_t stream);
+
+// CRC of one buffer: combine n_tiles registers, then run the register over `tail_bytes` more
+// bytes at `tail`, then apply the preset/complement term `affine`.
+hipError_t launch_finish_crc(const uint32_t* partial, uint32_t n_tiles, uint32_t x_tile,
+                             const uint8_t* tail, uint32_t tail_bytes, uint32_t affine,
+                             uint32_t* out, hipStream_t stream);
+
+hipError_t launch_copy(void* dst, const void* src, uint64_t nbytes, hipStream_t stream);
+
+// Fills tab[4][256] (host) with the byte tables of multiplication by x^8192.
+void build_tab_u(uint32_t* tab);
+
+}  // namespace ffsnap

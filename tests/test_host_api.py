@@ -1,0 +1,136 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, validates
+arguments, and lays snapshots out as defined.  No kernel runs here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_03644_amd import binding as ff
+from paper_2512_03644_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "ffsnap.h")).read()
+    declared = set(re.findall(r"\b(ff_[a-z0-9_]+)\s*\(", header))
+    declared -= {"ff_plan"}
+    assert declared == set(ff.EXPORTS)
+    L = ff.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def _host_plan(tensors, chunk, **kw):
+    return ff.ff_snapshot_plan(tensors, chunk, flags=ff.FF_PLAN_HOST_ONLY, **kw)
+
+
+def test_layout_matches_definition_and_oracle_sizes(oracle):
+    shard = wl.param_shard("s", [1000, 1, 77, 4096, 33333], 4096, 3, "cpu", tiny_recipe=True)
+    plan = ff.plan_for_shard(shard, flags=ff.FF_PLAN_HOST_ONLY)
+    n_el = sum(p.master.numel() for p in shard.params)
+    assert plan.payload_bytes == 14 * n_el == shard.payload_bytes   # size law, section 4.2
+    assert plan.num_chunks == shard.num_chunks == oracle.num_chunks(
+        [wl.numpy_alias(t) for t in shard.segments], 4096)
+    assert plan.buffer_bytes == plan.num_chunks * 4096 and plan.chunk_bytes == 4096
+    assert plan.num_segments == 20 and plan.num_params == 5
+    off = 0
+    for i, t in enumerate(shard.segments):
+        b, e = plan.segment_range(i)
+        assert (b, e) == (off, off + t.numel() * t.element_size())
+        off = e
+    # layout id: CRC32C over (chunk_bytes, nbytes...) little-endian uint64 -- oracle's CRC agrees
+    key = np.array([4096] + [t.numel() * t.element_size() for t in shard.segments], dtype="<u8")
+    assert plan.layout_id == oracle.crc32c(key.view(np.uint8))
+    # razor'd list (master, m, v only): 12 bytes per parameter
+    razored = [t for p in shard.params for t in (p.master, p.m, p.v)]
+    assert _host_plan(razored, 4096).payload_bytes == 12 * n_el
+
+
+def test_layout_id_depends_on_sizes_and_chunking():
+    a = torch.zeros(100, dtype=torch.float32)
+    b = torch.zeros(50, dtype=torch.bfloat16)
+    base = _host_plan([a, b], 1024).layout_id
+    assert _host_plan([a, b], 2048).layout_id != base
+    assert _host_plan([b, a], 1024).layout_id != base
+    assert _host_plan([a, b, torch.zeros(0)], 1024).layout_id == base   # empty segment skipped
+    assert _host_plan([a.clone(), b.clone()], 1024).layout_id == base   # addresses do not matter
+
+
+def test_argument_validation():
+    a = torch.zeros(64, dtype=torch.float32)
+    L = ff.lib()
+    out = ctypes.c_void_p()
+    segs = ff.make_segments([a])
+    H = ff.FF_PLAN_HOST_ONLY
+
+    def plan_status(segs, n, chunk, flags=H):
+        return L.ff_snapshot_plan(segs, n, chunk, flags, ctypes.byref(out))
+
+    assert plan_status(segs, 1, 1000) == ff.FF_ERR_INVALID           # not a power of two
+    assert plan_status(segs, 1, 512) == ff.FF_ERR_INVALID            # below the minimum
+    assert plan_status(segs, 1, 1 << 31) == ff.FF_ERR_INVALID        # above the maximum
+    assert plan_status(None, 1, 1024) == ff.FF_ERR_NULL
+    assert L.ff_snapshot_plan(segs, 1, 1024, H, None) == ff.FF_ERR_NULL
+    assert plan_status(segs, 1, 1024, H | 2) == ff.FF_ERR_INVALID    # unknown flag
+    assert plan_status(segs, 0, 1024) == ff.FF_ERR_EMPTY
+    empty = ff.make_segments([torch.zeros(0)])
+    assert plan_status(empty, 1, 1024) == ff.FF_ERR_EMPTY
+    for field, value, want in (("dtype", 7, ff.FF_ERR_INVALID), ("kind", 9, ff.FF_ERR_INVALID),
+                               ("reserved", 1, ff.FF_ERR_INVALID), ("nbytes", 6, ff.FF_ERR_INVALID),
+                               ("ptr", None, ff.FF_ERR_NULL),
+                               ("ptr", a.data_ptr() + 2, ff.FF_ERR_INVALID)):
+        s = ff.make_segments([a])
+        setattr(s[0], field, value)
+        assert plan_status(s, 1, 1024) == want, field
+        assert not out.value
+    # a bf16 segment may start on any even address
+    s = ff.make_segments([a.view(torch.bfloat16)[1:3]])
+    assert plan_status(s, 1, 1024) == ff.FF_OK
+    L.ff_plan_destroy(out)
+    assert "pointer" in ff.ff_strerror(ff.FF_ERR_NULL) and ff.ff_strerror(0) == "ok"
+
+
+def test_host_only_plan_refuses_device_work():
+    a = torch.zeros(1024, dtype=torch.float32)
+    plan = _host_plan([a], 1024)
+    L = ff.lib()
+    dummy = ctypes.c_void_p(16)
+    assert L.ff_pack(plan.handle, dummy, dummy, None) == ff.FF_ERR_HOST_ONLY
+    assert L.ff_restore(plan.handle, dummy, dummy, dummy, dummy, 0, None) == ff.FF_ERR_HOST_ONLY
+    assert L.ff_pack(None, dummy, dummy, None) == ff.FF_ERR_NULL
+    assert L.ff_plan_segment_range(plan.handle, 5, ctypes.byref(ctypes.c_uint64()),
+                                   ctypes.byref(ctypes.c_uint64())) == ff.FF_ERR_INVALID
+
+
+def test_parameter_groups():
+    shard = wl.param_shard("s", [10, 20], 1024, 3, "cpu")
+    assert ff.plan_for_shard(shard, flags=ff.FF_PLAN_HOST_ONLY).num_params == 2
+    # an incomplete group: the plan still packs, but offers no parameter groups to the fused step
+    kinds = [ff.FF_KIND_W16, ff.FF_KIND_MASTER, ff.FF_KIND_M]
+    p = shard.params[0]
+    plan = _host_plan([p.w16, p.master, p.m], 1024, kinds=kinds, param_ids=[0, 0, 0])
+    assert plan.num_params == 0 and plan.payload_bytes == 10 * 10
+
+
+def test_fold_relations_are_multiples_of_the_generator(oracle):
+    # every tap relation in fold_taps.h: x^(32*(S*NE+f)) == sum_k x^(32*(S*e_k+f_k)) mod P,
+    # evaluated with the oracle's zero-byte shift (x^(8n) = shift(0x80000000, n))
+    text = open(os.path.join(ROOT, "paper_2512_03644_amd", "csrc", "fold_taps.h")).read()
+    for body in re.findall(r"struct \w+ \{\n(.*?)\n\};", text, flags=re.S):
+        val = {k: int(v) for k, v in re.findall(r"constexpr int (\w+) = (\d+);", body)}
+        tabs = {}
+        for name, init in re.findall(r"(TAP_[EF])\[NF\]\[NTAP\] = \{(.*)\};", body):
+            tabs[name] = [[int(x) for x in row.split(",")] for row in re.findall(r"\{([\d, ]+)\}", init)]
+        S, NE, NF, NT = val["STRIDE"], val["NE"], val["NF"], val["NTAP"]
+        assert S * 4 == val["ROW_BYTES"] and len(tabs["TAP_E"]) == NF
+        for f in range(NF):
+            acc = oracle.crc_shift(0x80000000, 4 * (S * NE + f))
+            assert len(tabs["TAP_E"][f]) == NT
+            for e, c in zip(tabs["TAP_E"][f], tabs["TAP_F"][f]):
+                assert 0 <= e < NE and 0 <= c < NF
+                acc ^= oracle.crc_shift(0x80000000, 4 * (S * e + c))
+            assert acc == 0
