@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Headline benchmark: snapshot pack+CRC and restore on a Llama-7B-shaped per-worker shard.
+
+One step = one pass of the whole hot path over the shard, state resident in HBM:
+    ff_adam_step_snapshot (when the library provides it)  ->  ff_pack  ->  ff_restore
+The shard is one 8-way data-parallel worker's slice of a 7B model: 226 parameters, bf16 weights
+plus fp32 master/m/v, 11.79 GB in 904 tensors, 4 MiB chunks (2812 chunks).
+
+Prints ONE JSON line.  `value` is the algorithmic HBM traffic of a step divided by its time
+(pack and restore each read and write every payload byte once: 2 B per payload byte; the fused
+Adam step moves 42 B per parameter).  `roofline` is the dominant kernel (the pack tile kernel):
+algorithmic bytes per launch over its HIP-event duration against the 8 TB/s HBM peak.
+`cpu_baseline` is the plain CPU oracle timed on this machine's host cores on a bounded sample of the
+same shard.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-adam", action="store_true", help="leave the fused optimizer step out")
+    ap.add_argument("--tile-log2", type=int, default=0, help="tuning: log2 of the tile size")
+    return ap.parse_args()
+
+
+def event_ms(fn, n, torch):
+    """Per-call durations of fn in ms, HIP events on the current stream."""
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(n)]
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return [a.elapsed_time(b) for a, b in evs]
+
+
+def cpu_baseline(shard, n_params, torch):
+    """The oracle's pack + restore on the first n_params parameter groups of the shard."""
+    import numpy as np
+    import oracle
+    from paper_2512_03644_amd import workloads as wl
+    segs = [wl.to_numpy_bytes(t) for p in shard.params[:n_params]
+            for t in (p.w16, p.master, p.m, p.v)]
+    nbytes = sum(s.size for s in segs)
+    cores = min(16, len(os.sched_getaffinity(0)))
+    oracle.lib()
+    t0 = time.perf_counter()
+    buf, crcs = oracle.pack(segs, shard.chunk_bytes, threads=cores)
+    t1 = time.perf_counter()
+    dst = [np.empty_like(s) for s in segs]
+    bad, n_bad = oracle.restore(dst, shard.chunk_bytes, buf, crcs, threads=cores)
+    t2 = time.perf_counter()
+    assert n_bad == 0
+    return {"value": round(4 * nbytes / (t2 - t0) / 1e9, 3), "unit": "GB/s", "cores": cores,
+            "kind": "oracle",
+            "sample": "first %d of %d parameter groups of the same shard (%.2f GB payload), "
+                      "oracle pack then restore, traffic counted as on the GPU (2 B per payload "
+                      "byte per pass); pack %.2f s, restore %.2f s wall"
+                      % (n_params, len(shard.params), nbytes / 1e9, t1 - t0, t2 - t1)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on one GPU; a worker's snapshot needs no other worker "
+              "(--gpus %d is not supported)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2512_03644_amd import binding as ff
+    from paper_2512_03644_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    ff.lib()
+
+    with_adam = not args.no_adam
+    shard = wl.config_llama7b(dev, with_grads=with_adam)
+    plan = ff.plan_for_shard(shard, tile_log2=args.tile_log2)
+    chunks, crcs, bad, n_bad = ff.alloc_outputs(plan, dev)
+    N = plan.payload_bytes
+    n_el = sum(p.master.numel() for p in shard.params)
+    hp = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1000)
+    grads = [p.grad for p in shard.params] if with_adam else None
+
+    def op_adam():
+        ff.ff_adam_step_snapshot(plan, grads, hp, chunks, crcs)
+
+    def op_pack():
+        ff.ff_pack(plan, chunks, crcs)
+
+    def op_restore():
+        ff.ff_restore(plan, chunks, crcs, bad, n_bad)
+
+    ops = [("pack", op_pack, 2 * N), ("restore", op_restore, 2 * N)]
+    if with_adam:
+        try:
+            op_adam()
+            torch.cuda.synchronize()
+            ops.insert(0, ("adam_snapshot", op_adam, 42 * n_el))
+        except ff.FFError as e:
+            print("bench.py: fused Adam step unavailable (%s); step = pack + restore" % e,
+                  file=sys.stderr)
+            with_adam = False
+    step_bytes = sum(b for _, _, b in ops)
+
+    def step():
+        for _, fn, _ in ops:
+            fn()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    assert int(n_bad.item()) == 0
+    ms_per_step = wall / args.steps * 1e3
+
+    # per-op durations (HIP events on the launch stream), and the copy ceiling beside them
+    detail = {}
+    for name, fn, nbytes in ops:
+        ts = event_ms(fn, max(args.steps, 5), torch)
+        avg = sum(ts) / len(ts)
+        detail[name] = {"avg_ms": round(avg, 4), "min_ms": round(min(ts), 4),
+                        "traffic_GBps": round(nbytes / avg / 1e6, 1),
+                        "frac_of_peak": round(nbytes / avg / 1e6 / HBM_PEAK_GBS, 4)}
+    detail["pack"]["payload_GBps"] = round(N / detail["pack"]["avg_ms"] / 1e6, 1)
+    detail["restore"]["payload_GBps"] = round(N / detail["restore"]["avg_ms"] / 1e6, 1)
+    src = torch.empty(N, dtype=torch.uint8, device=dev)
+    ts = event_ms(lambda: ff.ff_copy_ceiling(chunks, src, N), 5, torch)
+    copy_gbs = 2 * N / (sum(ts) / len(ts)) / 1e6
+    del src
+
+    pack_ms = detail["pack"]["avg_ms"]
+    achieved = 2 * N / pack_ms / 1e6
+    roofline = {"bound": "hbm", "kernel": "tile_kernel<pack>", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": None,
+                "copy_ceiling_GBps": round(copy_gbs, 1),
+                "frac_of_copy_ceiling": round(achieved / copy_gbs, 4)}
+
+    out = {"metric": "snapshot pack+CRC and restore GB/s, % of HBM peak, 7B-shaped shard",
+           "value": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "u8" if not with_adam else "u8+f32", "data": "synthetic",
+           "config": {"workload": "llama7b-dp8 shard: 226 params, bf16 w + fp32 master/m/v, "
+                                  "%d B payload, 904 segments, 4 MiB chunks (%d)"
+                                  % (N, plan.num_chunks),
+                      "step": " + ".join(n for n, _, _ in ops),
+                      "bytes_per_step": step_bytes},
+           "pct_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS * 100, 2),
+           "ops": detail, "roofline": roofline}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shard, 32, torch)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
