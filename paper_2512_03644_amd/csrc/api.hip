@@ -104,7 +104,7 @@ int ff_snapshot_plan(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_byt
     *out = nullptr;
     // bits 8..15 of flags: log2 of the tile size in bytes (0 = default), a tuning knob
     const unsigned tile_log2 = (flags >> 8) & 0xFFu;
-    if (flags & ~(FF_PLAN_HOST_ONLY | 0xFF00u)) return FF_ERR_INVALID;
+    if (flags & ~(FF_PLAN_HOST_ONLY | 0xFF00u | 0x70000u)) return FF_ERR_INVALID;
     ff_plan* p = new (std::nothrow) ff_plan();
     if (!p) return FF_ERR_NOMEM;
     int rc;
@@ -129,6 +129,8 @@ int ff_snapshot_plan(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_byt
     t.lead_rows = 0;
     t.n_tiles = static_cast<uint32_t>(L.n_tiles);
     fill_constants(t);
+    // bits 16..18: bit 18 set = take bits 16..17 as the cache-hint selector (tuning knob)
+    if (flags & 0x40000u) t.hint = (flags >> 16) & 3u;
     if (L.n_tiles > 0xFFFFFFF0ull) {
         delete p;
         return FF_ERR_INVALID;

@@ -37,11 +37,13 @@ struct __attribute__((packed, aligned(2))) U4Unaligned {
 
 constexpr int kWaveSize = 64;
 constexpr int kWavesPerBlock = 4;
-constexpr int kRowBytes = Fold16::ROW_BYTES;
-constexpr int kNE = Fold16::NE;
-constexpr int kNF = Fold16::NF;
-constexpr int kDepth = 8;  // rows in flight per wavefront
+using Fold = Fold16x16;
+constexpr int kRowBytes = Fold::ROW_BYTES;
+constexpr int kNE = Fold::NE;
+constexpr int kNF = Fold::NF;
+constexpr int kDepth = 16;  // rows in flight per wavefront
 static_assert(kNE % kDepth == 0, "queue slots must repeat with the state rotation");
+static_assert(kNF == 4 && kRowBytes == 1024, "one 16-byte word per lane per row");
 
 template <class Fn, int... Is>
 __device__ __forceinline__ void static_for_impl(Fn&& fn, std::integer_sequence<int, Is...>)
@@ -54,26 +56,37 @@ __device__ __forceinline__ void static_for(Fn&& fn)
     static_for_impl(fn, std::make_integer_sequence<int, N>{});
 }
 
+typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
+
+// Segment side: 16 bytes at any even address.  Buffer side: 16-byte aligned.  NT marks the
+// access non-temporal (streaming data that will not be reused).
+template <bool NT = false>
 __device__ __forceinline__ u32x4 load16_unaligned(const uint8_t* p)
 {
-    U4Unaligned v = *reinterpret_cast<const U4Unaligned*>(p);
-    u32x4 r;
-    r.x = v.x; r.y = v.y; r.z = v.z; r.w = v.w;
-    return r;
+    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4_a2*>(p));
+    return *reinterpret_cast<const u32x4_a2*>(p);
 }
+template <bool NT = false>
 __device__ __forceinline__ void store16_unaligned(uint8_t* p, u32x4 w)
 {
-    U4Unaligned v;
-    v.x = w.x; v.y = w.y; v.z = w.z; v.w = w.w;
-    *reinterpret_cast<U4Unaligned*>(p) = v;
+    if (NT)
+        __builtin_nontemporal_store(w, reinterpret_cast<u32x4_a2*>(p));
+    else
+        *reinterpret_cast<u32x4_a2*>(p) = w;
 }
+template <bool NT = true>
 __device__ __forceinline__ u32x4 load16_stream(const uint8_t* p)
 {
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return *reinterpret_cast<const u32x4*>(p);
 }
+template <bool NT = true>
 __device__ __forceinline__ void store16_stream(uint8_t* p, u32x4 w)
 {
-    __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(p));
+    if (NT)
+        __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(p));
+    else
+        *reinterpret_cast<u32x4*>(p) = w;
 }
 
 // ---- segment cursor (wave-uniform) -----------------------------------------------------------
@@ -205,9 +218,9 @@ __device__ __forceinline__ void fold_row(uint32_t (&S)[kNE][kNF], u32x4 w)
     S[top][1] = w.z;
     S[top][0] = w.w;
     static_for<kNF>([&](auto f) {
-        static_for<Fold16::NTAP>([&](auto k) {
-            constexpr int e = Fold16::TAP_E[f][k];
-            constexpr int c = Fold16::TAP_F[f][k];
+        static_for<Fold::NTAP>([&](auto k) {
+            constexpr int e = Fold::TAP_E[f][k];
+            constexpr int c = Fold::TAP_F[f][k];
             constexpr int p = (e - (J + 1) + 2 * kNE) % kNE;
             S[p][c] ^= t[f];
         });
@@ -245,7 +258,11 @@ __device__ __forceinline__ uint32_t reduce_tile(const uint32_t (&S)[kNE][kNF], c
 
 // ---- tile kernel -------------------------------------------------------------------------------
 
-template <int MODE>
+// Rows are handled in groups of kNE (one full rotation of the state registers).  A group whose
+// rows, and the rows it prefetches, all lie inside one segment runs as straight-line code: no
+// branch sits between the loads, so up to kDepth of them stay in flight per wavefront.  Any other
+// group (tile start with virtual rows, segment boundary, end of payload) takes the guarded path.
+template <int MODE, int HINT>
 __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
     const uint64_t* __restrict__ seg_off, const uint64_t* __restrict__ seg_ptr,
     const uint32_t* __restrict__ tile_first_seg, const uint32_t* __restrict__ tab_u_global,
@@ -270,36 +287,50 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
     const int pad = groups * kNE - R;  // virtual zero rows in front: they leave the state at 0
     const uint64_t s_base = static_cast<uint64_t>(row_begin) * kRowBytes;
     const uint32_t lane16 = 16u * lane;
+    constexpr bool kSegNT = (HINT & 1) != 0;  // non-temporal accesses on the tensor side
+    constexpr bool kBufNT = (HINT & 2) != 0;  // non-temporal accesses on the chunk-buffer side
 
     Cursor cin, cout;  // pack reads through cin; restore writes through cout
     if (MODE == kPack) cursor_init(cin, seg_off, seg_ptr, tile_first_seg[tile]);
     if (MODE == kRestore) cursor_init(cout, seg_off, seg_ptr, tile_first_seg[tile]);
 
+    auto row_offset = [&](int r) { return s_base + static_cast<uint64_t>(r) * kRowBytes; };
+
+    // guarded single-row access
     auto load_row = [&](int r) -> u32x4 {
-        const uint64_t s = s_base + static_cast<uint64_t>(r) * kRowBytes;
+        const uint64_t s = row_offset(r);
         if (MODE == kPack) {
             if (s >= T.payload) return u32x4{0, 0, 0, 0};
             cursor_seek(cin, seg_off, seg_ptr, T.n_seg, s);
             if (s + kRowBytes <= cin.b)
-                return load16_unaligned(reinterpret_cast<const uint8_t*>(cin.base + (s - cin.a)) +
+                return load16_unaligned<kSegNT>(reinterpret_cast<const uint8_t*>(cin.base + (s - cin.a)) +
                                         lane16);
             return gather_row_slow(seg_off, seg_ptr, T.n_seg, cin.si, s, T.payload, lane);
         } else {
-            return load16_stream(chunks + s + lane16);
+            return load16_stream<kBufNT>(chunks + s + lane16);
         }
     };
     auto sink_row = [&](int r, u32x4 w) {
-        const uint64_t s = s_base + static_cast<uint64_t>(r) * kRowBytes;
+        const uint64_t s = row_offset(r);
         if (MODE == kPack) {
-            store16_stream(chunks + s + lane16, w);
+            store16_stream<kBufNT>(chunks + s + lane16, w);
         } else if (MODE == kRestore) {
             if (s >= T.payload) return;
             cursor_seek(cout, seg_off, seg_ptr, T.n_seg, s);
             if (s + kRowBytes <= cout.b)
-                store16_unaligned(reinterpret_cast<uint8_t*>(cout.base + (s - cout.a)) + lane16, w);
+                store16_unaligned<kSegNT>(reinterpret_cast<uint8_t*>(cout.base + (s - cout.a)) + lane16, w);
             else
                 scatter_row_slow(seg_off, seg_ptr, T.n_seg, cout.si, s, T.payload, lane, w);
         }
+    };
+    // Is the stream range [s, s + n rows) inside one segment?  On success *p is the lane's
+    // address of the first row.  (Buffer-side ranges always are.)
+    auto span_in_segment = [&](Cursor& c, uint64_t s, int n, const uint8_t** p) -> bool {
+        if (s >= T.payload) return false;
+        cursor_seek(c, seg_off, seg_ptr, T.n_seg, s);
+        if (s + static_cast<uint64_t>(n) * kRowBytes > c.b) return false;
+        *p = reinterpret_cast<const uint8_t*>(c.base + (s - c.a)) + lane16;
+        return true;
     };
 
     uint32_t S[kNE][kNF];
@@ -307,16 +338,82 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
 
     // queue slot of row r is (r + pad) mod kDepth; fill the first kDepth rows
     u32x4 q[kDepth];
-    static_for<kDepth>([&](auto k) {
-        const int r = ((k - pad) % kDepth + kDepth) % kDepth;
-        q[k] = u32x4{0, 0, 0, 0};
-        if (r < R) q[k] = load_row(r);
-    });
+    {
+        const uint8_t* lp = chunks + s_base + lane16;
+        bool fast = (pad == 0) && (R >= kDepth);
+        if (MODE == kPack) fast = fast && span_in_segment(cin, s_base, kDepth, &lp);
+        if (fast) {
+            static_for<kDepth>([&](auto k) {
+                q[k] = (MODE == kPack) ? load16_unaligned<kSegNT>(lp + k * kRowBytes)
+                                       : load16_stream<kBufNT>(lp + k * kRowBytes);
+            });
+        } else {
+            static_for<kDepth>([&](auto k) {
+                const int r = ((k - pad) % kDepth + kDepth) % kDepth;
+                q[k] = u32x4{0, 0, 0, 0};
+                if (r < R) q[k] = load_row(r);
+            });
+        }
+    }
 
-    for (int g = 0; g < groups; g++) {
+    // How many whole groups fit into n_rows rows / into the rest of a segment.
+    auto groups_in = [&](uint64_t bytes) { return static_cast<int>(bytes / (uint64_t(kNE) * kRowBytes)); };
+
+    int g = 0;
+    while (g < groups) {
+        const int r0 = g * kNE - pad;  // first row of the group (negative: virtual rows)
+        // Steady run: n consecutive groups whose rows are real, whose kNE prefetched rows exist
+        // and come from one segment (pack), and whose rows go to one segment (restore).
+        int n = 0;
+        const uint8_t* lp = chunks + row_offset(r0 + kDepth) + lane16;  // rows to prefetch
+        const uint8_t* sp = chunks + row_offset(r0) + lane16;           // rows to write
+        if (r0 >= 0 && r0 + kDepth + kNE <= R) {
+            n = (R - kDepth - r0) / kNE;
+            if (MODE == kPack) {
+                const uint64_t s = row_offset(r0 + kDepth);
+                if (span_in_segment(cin, s, kNE, &lp)) {
+                    const int m = groups_in(cin.b - s);
+                    n = n < m ? n : m;
+                } else {
+                    n = 0;
+                }
+            }
+            if (MODE == kRestore && n > 0) {
+                const uint64_t s = row_offset(r0);
+                if (span_in_segment(cout, s, kNE, &sp)) {
+                    const int m = groups_in(cout.b - s);
+                    n = n < m ? n : m;
+                } else {
+                    n = 0;
+                }
+            }
+        }
+        if (n > 0) {
+            uint8_t* wp = const_cast<uint8_t*>(sp);
+            for (int i = 0; i < n; i++) {
+                static_for<kNE>([&](auto Jc) {
+                    constexpr int J = Jc;
+                    const u32x4 w = q[J % kDepth];
+                    if (MODE == kPack) store16_stream<kBufNT>(wp + J * kRowBytes, w);
+                    if (MODE == kRestore) store16_unaligned<kSegNT>(wp + J * kRowBytes, w);
+                    fold_row<J>(S, w);
+                    // the refill is issued after the last use of w and the rows stay in program
+                    // order, so the slot is reloaded in place and kDepth loads stay in flight
+                    __builtin_amdgcn_sched_barrier(0);
+                    q[J % kDepth] = (MODE == kPack) ? load16_unaligned<kSegNT>(lp + J * kRowBytes)
+                                                    : load16_stream<kBufNT>(lp + J * kRowBytes);
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+                lp += kNE * kRowBytes;
+                wp += kNE * kRowBytes;
+            }
+            g += n;
+            continue;
+        }
+        // guarded group: virtual rows, segment boundaries, end of payload, end of tile
         static_for<kNE>([&](auto Jc) {
             constexpr int J = Jc;
-            const int r = g * kNE + J - pad;
+            const int r = r0 + J;
             if (r >= 0) {
                 const u32x4 w = q[J % kDepth];
                 if (r + kDepth < R) q[J % kDepth] = load_row(r + kDepth);
@@ -324,6 +421,7 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
                 fold_row<J>(S, w);
             }
         });
+        g++;
     }
 
     const uint32_t reg = reduce_tile(S, tab, T.x32, T.z);
@@ -401,6 +499,22 @@ void build_tab_u(uint32_t* tab)
         for (uint32_t b = 0; b < 256; b++) tab[k * 256 + b] = gf2_mul(b << (8 * k), u);
 }
 
+template <int MODE>
+static void launch_tiles_hint(int hint, dim3 grid, dim3 block, hipStream_t stream, const TileTables& t,
+                              uint8_t* c, uint64_t* n_bad)
+{
+#define FF_LAUNCH(H)                                                                             \
+    hipLaunchKernelGGL((tile_kernel<MODE, H>), grid, block, 0, stream, t.seg_off, t.seg_ptr,      \
+                       t.tile_first_seg, t.tab_u, t.partial, c, n_bad, t)
+    switch (hint & 3) {
+    case 0: FF_LAUNCH(0); break;
+    case 1: FF_LAUNCH(1); break;
+    case 2: FF_LAUNCH(2); break;
+    default: FF_LAUNCH(3); break;
+    }
+#undef FF_LAUNCH
+}
+
 hipError_t launch_tiles(TileMode mode, const TileTables& t, void* chunks, uint64_t* n_bad,
                         hipStream_t stream)
 {
@@ -409,18 +523,9 @@ hipError_t launch_tiles(TileMode mode, const TileTables& t, void* chunks, uint64
     const dim3 block(kWaveSize * kWavesPerBlock);
     uint8_t* c = static_cast<uint8_t*>(chunks);
     switch (mode) {
-    case kPack:
-        hipLaunchKernelGGL(tile_kernel<kPack>, grid, block, 0, stream, t.seg_off, t.seg_ptr,
-                           t.tile_first_seg, t.tab_u, t.partial, c, n_bad, t);
-        break;
-    case kRestore:
-        hipLaunchKernelGGL(tile_kernel<kRestore>, grid, block, 0, stream, t.seg_off, t.seg_ptr,
-                           t.tile_first_seg, t.tab_u, t.partial, c, n_bad, t);
-        break;
-    case kVerify:
-        hipLaunchKernelGGL(tile_kernel<kVerify>, grid, block, 0, stream, t.seg_off, t.seg_ptr,
-                           t.tile_first_seg, t.tab_u, t.partial, c, n_bad, t);
-        break;
+    case kPack: launch_tiles_hint<kPack>(t.hint, grid, block, stream, t, c, n_bad); break;
+    case kRestore: launch_tiles_hint<kRestore>(t.hint, grid, block, stream, t, c, n_bad); break;
+    case kVerify: launch_tiles_hint<kVerify>(t.hint, grid, block, stream, t, c, n_bad); break;
     }
     return hipGetLastError();
 }

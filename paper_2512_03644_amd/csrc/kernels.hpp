@@ -21,6 +21,7 @@ struct TileTables {
     uint32_t n_tiles = 0;
     uint32_t x32 = 0;                         // x^32 mod P
     uint32_t z[6] = {0, 0, 0, 0, 0, 0};       // x^(128 * 2^l) mod P
+    uint32_t hint = 3;                        // bit 0: non-temporal tensor-side accesses, bit 1: buffer-side
 };
 
 enum TileMode { kPack = 0, kRestore = 1, kVerify = 2 };
