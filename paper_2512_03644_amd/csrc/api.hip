@@ -9,6 +9,7 @@
 
 #include "../../include/ffsnap.h"
 #include "gf2.h"
+#include "fused.hpp"
 #include "kernels.hpp"
 #include "layout.hpp"
 
@@ -22,6 +23,11 @@ struct ff_plan {
     TileTables tables;
     uint32_t x_tile = 0;  // x^(8 * tile_bytes)
     uint32_t affine = 0;  // preset/complement term of a chunk_bytes-long CRC
+    // fused optimizer step (only when every parameter group is complete)
+    const WorkTile* work = nullptr;
+    uint32_t n_work = 0;
+    uint64_t* grads = nullptr;        // [n_params] device copy of the caller's gradient pointers
+    const uint32_t* fused_tabs = nullptr;
 };
 
 namespace {
@@ -57,7 +63,13 @@ int upload_tables(ff_plan* p)
     const uint64_t o_first = align_up(o_ptr + n * 8, 256);
     const uint64_t o_tab = align_up(o_first + L.n_tiles * 4, 256);
     const uint64_t o_partial = align_up(o_tab + 1024 * 4, 256);
-    const uint64_t total = align_up(o_partial + L.n_tiles * 4, 256);
+    std::vector<WorkTile> work;
+    if (L.adam_ok && !L.params.empty()) build_work_tiles(L, work);
+    if (work.size() > 0xFFFFFFF0ull) return FF_ERR_INVALID;
+    const uint64_t o_work = align_up(o_partial + L.n_tiles * 4, 256);
+    const uint64_t o_grads = align_up(o_work + work.size() * sizeof(WorkTile), 256);
+    const uint64_t o_ftabs = align_up(o_grads + L.params.size() * 8, 256);
+    const uint64_t total = align_up(o_ftabs + 2048 * 4, 256);
 
     std::vector<unsigned char> host(total, 0);
     uint64_t* h_off = reinterpret_cast<uint64_t*>(host.data() + o_off);
@@ -69,6 +81,9 @@ int upload_tables(ff_plan* p)
     h_off[n] = L.payload;
     std::memcpy(host.data() + o_first, L.tile_first_seg.data(), L.n_tiles * 4);
     build_tab_u(reinterpret_cast<uint32_t*>(host.data() + o_tab));
+    if (!work.empty()) std::memcpy(host.data() + o_work, work.data(), work.size() * sizeof(WorkTile));
+    build_tab(reinterpret_cast<uint32_t*>(host.data() + o_ftabs), 1024);
+    build_tab(reinterpret_cast<uint32_t*>(host.data() + o_ftabs) + 1024, 512);
 
     FF_HIP_TRY(hipGetDevice(&p->device));
     hipError_t e = hipMalloc(&p->dev_block, total);
@@ -83,6 +98,10 @@ int upload_tables(ff_plan* p)
     t.tile_first_seg = reinterpret_cast<const uint32_t*>(d + o_first);
     t.tab_u = reinterpret_cast<const uint32_t*>(d + o_tab);
     t.partial = reinterpret_cast<uint32_t*>(d + o_partial);
+    p->work = reinterpret_cast<const WorkTile*>(d + o_work);
+    p->n_work = static_cast<uint32_t>(work.size());
+    p->grads = reinterpret_cast<uint64_t*>(d + o_grads);
+    p->fused_tabs = reinterpret_cast<const uint32_t*>(d + o_ftabs);
     return FF_OK;
 }
 
@@ -213,8 +232,36 @@ int ff_adam_step_snapshot(const ff_plan* p, const void* const* grads, const ff_a
     int rc = check_device_call(p);
     if (rc != FF_OK) return rc;
     if (!grads || !hp || !chunks || !crcs) return FF_ERR_NULL;
-    (void)hip_stream;
-    return FF_ERR_INVALID;  // fused step: not wired up yet
+    const Layout& L = p->layout;
+    if (!L.adam_ok || L.params.empty() || hp->step == 0) return FF_ERR_INVALID;
+    if (reinterpret_cast<uint64_t>(chunks) % 16 || reinterpret_cast<uint64_t>(crcs) % 4)
+        return FF_ERR_INVALID;
+    for (size_t i = 0; i < L.params.size(); i++) {
+        if (!grads[i]) return FF_ERR_NULL;
+        if (reinterpret_cast<uint64_t>(grads[i]) % 2) return FF_ERR_INVALID;
+    }
+    FusedConsts c;
+    fill_fused_crc_consts(c);
+    {
+        // shared scalars: evaluated in double from the fp32 hyper-parameters, rounded once
+        const double lr = hp->lr, b1 = hp->beta1, b2 = hp->beta2, wd = hp->weight_decay;
+        const double t = static_cast<double>(hp->step);
+        c.adam.decay = static_cast<float>(1.0 - lr * wd);
+        c.adam.b1 = hp->beta1;
+        c.adam.omb1 = static_cast<float>(1.0 - b1);
+        c.adam.b2 = hp->beta2;
+        c.adam.omb2 = static_cast<float>(1.0 - b2);
+        c.adam.step_size = static_cast<float>(lr / (1.0 - std::pow(b1, t)));
+        c.adam.bc2s = static_cast<float>(std::sqrt(1.0 - std::pow(b2, t)));
+        c.adam.eps = hp->eps;
+    }
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    // the pointer array is staged by the runtime before the call returns
+    FF_HIP_TRY(hipMemcpyAsync(p->grads, grads, L.params.size() * sizeof(uint64_t),
+                              hipMemcpyHostToDevice, s));
+    FF_HIP_TRY(launch_fused(p->work, p->n_work, p->grads, p->fused_tabs, chunks, crcs, L.n_chunks,
+                            L.payload, L.buffer_bytes, p->affine, c, s));
+    return FF_OK;
 }
 
 int ff_crc32c(const void* dev_buf, uint64_t nbytes, uint32_t* dev_out, void* hip_stream)

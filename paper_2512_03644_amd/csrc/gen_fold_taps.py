@@ -53,7 +53,58 @@ def xpow(e):
     return r
 
 
+def solve_min_weight(S, F, NE):
+    """For a small surplus of candidates over the 32 dimensions of the residue space: solve the
+    linear system by Gaussian elimination, then walk the whole solution set (one particular
+    solution plus the null space) and keep the representation with the fewest terms."""
+    cand = [S * e + f for e in range(NE) for f in range(F)]
+    n = len(cand)
+    vecs = [xpow(32 * E) for E in cand]
+    basis = {}     # highest bit -> (value, mask of candidates)
+    null = []      # masks of candidate subsets that XOR to zero
+    for i, v in enumerate(vecs):
+        m = 1 << i
+        while v:
+            hb = v.bit_length() - 1
+            if hb in basis:
+                v ^= basis[hb][0]
+                m ^= basis[hb][1]
+            else:
+                basis[hb] = (v, m)
+                break
+        if not v:
+            null.append(m)
+    assert len(null) <= 20, "too many candidates for exhaustive enumeration"
+    out = []
+    for f in range(F):
+        v, m = xpow(32 * (S * NE + f)), 0
+        while v:
+            hb = v.bit_length() - 1
+            if hb not in basis:
+                raise SystemExit("target outside the span for S=%d F=%d NE=%d f=%d" % (S, F, NE, f))
+            v ^= basis[hb][0]
+            m ^= basis[hb][1]
+        best = None
+        for k in range(1 << len(null)):
+            mm = m
+            for j, nm in enumerate(null):
+                if (k >> j) & 1:
+                    mm ^= nm
+            key = (bin(mm).count("1"), mm)
+            if best is None or key < best:
+                best = key
+        taps = [i for i in range(n) if (best[1] >> i) & 1]
+        acc = xpow(32 * (S * NE + f))
+        for i in taps:
+            acc ^= vecs[i]
+        assert acc == 0
+        out.append([(cand[i] // S, cand[i] % S) for i in taps])
+    return out
+
+
 def search(S, F, NE, ntaps):
+    if ntaps == 0:
+        return solve_min_weight(S, F, NE)
     cand = [S * e + f for e in range(NE) for f in range(F)]
     r = np.array([xpow(32 * E) for E in cand], dtype=np.uint64)
     n = len(cand)
@@ -101,6 +152,9 @@ SETS = [
     # name, row bytes, dwords per lane, NE, taps
     ("Fold16x24", 1024, 4, 24, 7),
     ("Fold16x16", 1024, 4, 16, 9),
+    # 0 = fewest terms found by exhaustive walk of the solution set (few candidates, small state)
+    ("Fold16x10", 1024, 4, 10, 0),
+    ("Fold8x20", 512, 2, 20, 0),
 ]
 
 
@@ -112,12 +166,15 @@ def emit(path):
     for name, row, F, NE, nt in SETS:
         S = row // 4
         taps = search(S, F, NE, nt)
+        nt = max(len(t) for t in taps)
+        used = [len(t) for t in taps]
+        taps = [t + [(255, 255)] * (nt - len(t)) for t in taps]  # 255 = unused slot
         lines += ["struct %s {" % name,
                   "    static constexpr int ROW_BYTES = %d;  // bytes one wavefront reads per step" % row,
                   "    static constexpr int STRIDE = %d;     // dword distance between a lane's rows" % S,
                   "    static constexpr int NF = %d;         // dwords per lane per row" % F,
                   "    static constexpr int NE = %d;         // rows of state" % NE,
-                  "    static constexpr int NTAP = %d;" % nt]
+                  "    static constexpr int NTAP = %d;       // slots per column (255 = unused)" % nt]
         for nm, sel in (("TAP_E", 0), ("TAP_F", 1)):
             rows = ["{" + ", ".join(str(t[sel]) for t in taps[f]) + "}" for f in range(F)]
             lines.append("    static constexpr unsigned char %s[NF][NTAP] = {%s};" % (nm, ", ".join(rows)))

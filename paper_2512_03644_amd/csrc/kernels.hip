@@ -20,22 +20,12 @@
 // term, which gives the standard CRC32C of the chunk.
 #include "kernels.hpp"
 
-#include <type_traits>
-#include <utility>
-
-#include "fold_taps.h"
-#include "gf2.h"
+#include "fold.h"
 
 namespace ffsnap {
 
 namespace {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-struct __attribute__((packed, aligned(2))) U4Unaligned {
-    uint32_t x, y, z, w;
-};
-
-constexpr int kWaveSize = 64;
 constexpr int kWavesPerBlock = 4;
 using Fold = Fold16x16;
 constexpr int kRowBytes = Fold::ROW_BYTES;
@@ -44,50 +34,6 @@ constexpr int kNF = Fold::NF;
 constexpr int kDepth = 16;  // rows in flight per wavefront
 static_assert(kNE % kDepth == 0, "queue slots must repeat with the state rotation");
 static_assert(kNF == 4 && kRowBytes == 1024, "one 16-byte word per lane per row");
-
-template <class Fn, int... Is>
-__device__ __forceinline__ void static_for_impl(Fn&& fn, std::integer_sequence<int, Is...>)
-{
-    (fn(std::integral_constant<int, Is>{}), ...);
-}
-template <int N, class Fn>
-__device__ __forceinline__ void static_for(Fn&& fn)
-{
-    static_for_impl(fn, std::make_integer_sequence<int, N>{});
-}
-
-typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
-
-// Segment side: 16 bytes at any even address.  Buffer side: 16-byte aligned.  NT marks the
-// access non-temporal (streaming data that will not be reused).
-template <bool NT = false>
-__device__ __forceinline__ u32x4 load16_unaligned(const uint8_t* p)
-{
-    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4_a2*>(p));
-    return *reinterpret_cast<const u32x4_a2*>(p);
-}
-template <bool NT = false>
-__device__ __forceinline__ void store16_unaligned(uint8_t* p, u32x4 w)
-{
-    if (NT)
-        __builtin_nontemporal_store(w, reinterpret_cast<u32x4_a2*>(p));
-    else
-        *reinterpret_cast<u32x4_a2*>(p) = w;
-}
-template <bool NT = true>
-__device__ __forceinline__ u32x4 load16_stream(const uint8_t* p)
-{
-    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-    return *reinterpret_cast<const u32x4*>(p);
-}
-template <bool NT = true>
-__device__ __forceinline__ void store16_stream(uint8_t* p, u32x4 w)
-{
-    if (NT)
-        __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(p));
-    else
-        *reinterpret_cast<u32x4*>(p) = w;
-}
 
 // ---- segment cursor (wave-uniform) -----------------------------------------------------------
 
@@ -202,58 +148,11 @@ __device__ __noinline__ void scatter_row_slow(const uint64_t* __restrict__ seg_o
     }
 }
 
-// ---- folding -----------------------------------------------------------------------------------
-
-// One row into the state.  J = number of rows folded since the rotation was last at zero
-// (modulo NE): physical register row p holds logical row (p + J) mod NE.
 template <int J>
-__device__ __forceinline__ void fold_row(uint32_t (&S)[kNE][kNF], u32x4 w)
+__device__ __forceinline__ void fold_word(uint32_t (&S)[kNE][kNF], u32x4 w)
 {
-    constexpr int top = (kNE - 1 - J + kNE) % kNE;  // logical row NE-1 before the shift
-    uint32_t t[kNF];
-    static_for<kNF>([&](auto f) { t[f] = S[top][f]; });
-    // the freed row becomes logical row 0: the new word, first dword = highest power
-    S[top][3] = w.x;
-    S[top][2] = w.y;
-    S[top][1] = w.z;
-    S[top][0] = w.w;
-    static_for<kNF>([&](auto f) {
-        static_for<Fold::NTAP>([&](auto k) {
-            constexpr int e = Fold::TAP_E[f][k];
-            constexpr int c = Fold::TAP_F[f][k];
-            constexpr int p = (e - (J + 1) + 2 * kNE) % kNE;
-            S[p][c] ^= t[f];
-        });
-    });
-}
-
-// Multiply by x^8192 with four byte tables in LDS.
-__device__ __forceinline__ uint32_t mul_u(const uint32_t* tab, uint32_t a)
-{
-    return tab[a & 0xFFu] ^ tab[256 + ((a >> 8) & 0xFFu)] ^ tab[512 + ((a >> 16) & 0xFFu)] ^
-           tab[768 + (a >> 24)];
-}
-
-// State of all lanes -> the register of the tile run from 0, valid in lane 0.
-__device__ __forceinline__ uint32_t reduce_tile(const uint32_t (&S)[kNE][kNF], const uint32_t* tab,
-                                                uint32_t x32, const uint32_t (&z)[6])
-{
-    uint32_t acc[kNF] = {0, 0, 0, 0};
-    static_for<kNE>([&](auto i) {
-        constexpr int e = kNE - 1 - i;
-        static_for<kNF>([&](auto f) { acc[f] = mul_u(tab, acc[f]) ^ S[e][f]; });
-    });
-    uint32_t v = acc[3];
-    v = gf2_mul(v, x32) ^ acc[2];
-    v = gf2_mul(v, x32) ^ acc[1];
-    v = gf2_mul(v, x32) ^ acc[0];
-    // lane l sits 16*(63-l) bytes before the end of the row
-#pragma unroll
-    for (int l = 0; l < 6; l++) {
-        const uint32_t other = __shfl_down(v, 1 << l, kWaveSize);
-        v = gf2_mul(v, z[l]) ^ other;
-    }
-    return gf2_mul(v, x32);  // the register carries the extra factor x^32
+    const uint32_t d[4] = {w.x, w.y, w.z, w.w};
+    fold_row<Fold, J>(S, d);
 }
 
 // ---- tile kernel -------------------------------------------------------------------------------
@@ -396,7 +295,7 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
                     const u32x4 w = q[J % kDepth];
                     if (MODE == kPack) store16_stream<kBufNT>(wp + J * kRowBytes, w);
                     if (MODE == kRestore) store16_unaligned<kSegNT>(wp + J * kRowBytes, w);
-                    fold_row<J>(S, w);
+                    fold_word<J>(S, w);
                     // the refill is issued after the last use of w and the rows stay in program
                     // order, so the slot is reloaded in place and kDepth loads stay in flight
                     __builtin_amdgcn_sched_barrier(0);
@@ -418,13 +317,13 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
                 const u32x4 w = q[J % kDepth];
                 if (r + kDepth < R) q[J % kDepth] = load_row(r + kDepth);
                 sink_row(r, w);
-                fold_row<J>(S, w);
+                fold_word<J>(S, w);
             }
         });
         g++;
     }
 
-    const uint32_t reg = reduce_tile(S, tab, T.x32, T.z);
+    const uint32_t reg = reduce_state<Fold>(S, tab, T.x32, T.z);
     if (lane == 0) partial[tile] = reg;
 }
 

@@ -95,4 +95,87 @@ int build_layout(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_bytes, 
     return FF_OK;
 }
 
+namespace {
+
+uint32_t shift_to_chunk_end(uint64_t piece_end, uint64_t chunk_bytes)
+{
+    const uint64_t chunk_end = (piece_end + chunk_bytes - 1) / chunk_bytes * chunk_bytes;
+    return gf2_xpow(8 * (chunk_end - piece_end));
+}
+
+}  // namespace
+
+void build_work_tiles(const Layout& L, std::vector<WorkTile>& out)
+{
+    out.clear();
+    const uint64_t C = L.chunk_bytes;
+    std::vector<bool> in_group(L.segs.size(), false);
+    for (size_t pi = 0; pi < L.params.size(); pi++) {
+        const Param& p = L.params[pi];
+        const uint64_t size[4] = {2, 4, 4, 4};
+        uint64_t off[4], ptr[4];
+        for (int x = 0; x < 4; x++) {
+            off[x] = L.segs[p.seg[x]].off;
+            ptr[x] = L.segs[p.seg[x]].ptr;
+            in_group[p.seg[x]] = true;
+        }
+        // cut points: (element, streams whose element is split there)
+        std::map<uint64_t, uint32_t> cuts;
+        cuts[0] = 0;
+        for (int x = 0; x < 4; x++) {
+            const uint64_t a = off[x], b = off[x] + size[x] * p.numel;
+            for (uint64_t B = (a / C + 1) * C; B < b; B += C) {
+                const uint64_t e = (B - a) / size[x];
+                uint32_t& m = cuts[e];
+                if ((B - a) % size[x]) m |= 1u << x;
+            }
+        }
+        for (auto it = cuts.begin(); it != cuts.end(); ++it) {
+            auto nx = std::next(it);
+            const uint64_t end = (nx == cuts.end()) ? p.numel : nx->first;
+            for (uint64_t e0 = it->first; e0 < end; e0 += kParamTileElems) {
+                WorkTile t{};
+                t.kind = kWorkParam;
+                t.grad_index = static_cast<uint32_t>(pi);
+                t.e0 = e0;
+                t.n = static_cast<uint32_t>(std::min<uint64_t>(kParamTileElems, end - e0));
+                t.head_split = (e0 == it->first) ? it->second : 0;
+                for (int x = 0; x < 4; x++) {
+                    t.ptr[x] = ptr[x] + size[x] * e0;
+                    t.soff[x] = off[x] + size[x] * e0;
+                    uint64_t begin = t.soff[x];
+                    const uint64_t stop = t.soff[x] + size[x] * t.n;
+                    if (t.head_split & (1u << x)) {
+                        t.chunk[3 + x] = static_cast<uint32_t>(begin / C);
+                        t.shift[3 + x] = kOne;  // the two head bytes end their chunk
+                        begin += 2;
+                    }
+                    t.chunk[x] = static_cast<uint32_t>(begin / C);
+                    t.shift[x] = shift_to_chunk_end(stop, C);
+                }
+                out.push_back(t);
+            }
+        }
+    }
+    for (size_t i = 0; i < L.segs.size(); i++) {
+        if (in_group[i]) continue;
+        const Seg& s = L.segs[i];
+        uint64_t pos = 0;
+        while (pos < s.nbytes) {
+            const uint64_t abs = s.off + pos;
+            uint64_t len = std::min<uint64_t>(kRawTileBytes, s.nbytes - pos);
+            len = std::min<uint64_t>(len, (abs / C + 1) * C - abs);
+            WorkTile t{};
+            t.kind = kWorkRaw;
+            t.n = static_cast<uint32_t>(len);
+            t.ptr[0] = s.ptr + pos;
+            t.soff[0] = abs;
+            t.chunk[0] = static_cast<uint32_t>(abs / C);
+            t.shift[0] = shift_to_chunk_end(abs + len, C);
+            out.push_back(t);
+            pos += len;
+        }
+    }
+}
+
 }  // namespace ffsnap

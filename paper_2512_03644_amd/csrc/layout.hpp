@@ -35,6 +35,32 @@ struct Layout {
                                            // (segs.size()-1 for tiles past the payload)
 };
 
+// Unit of work of the fused optimizer step: a run of elements of one parameter group (its four
+// streams w16/master/m/v), or a run of bytes of a RAW segment.  Runs are cut wherever one of
+// their streams crosses a chunk boundary, so each stream of a tile lies inside one chunk and
+// adds one term ("piece") to that chunk's CRC: register(piece) * x^(8 * bytes from the end of
+// the piece to the end of the chunk).  An fp32 element that straddles a chunk boundary (its
+// stream offset is 2 mod 4) starts a tile; its first two bytes form a separate "head" piece
+// that ends the previous chunk.
+struct WorkTile {
+    uint64_t ptr[4];    // addresses of the tile's first element: w16, master, m, v (RAW: ptr[0])
+    uint64_t soff[4];   // stream offsets of the tile's first byte in each stream
+    uint32_t chunk[7];  // pieces 0..3: the four streams; 4..6: head pieces of master, m, v
+    uint32_t shift[7];  // x^(8 * distance to the chunk end) mod P; 0 = piece absent
+    uint64_t e0;        // first element within the parameter (indexes the gradient)
+    uint32_t n;         // elements (parameter tile) or bytes (RAW tile)
+    uint32_t kind;      // 0 = parameter group, 1 = RAW
+    uint32_t grad_index;
+    uint32_t head_split;  // bit x set: the first element of stream x is split as described
+};
+
+constexpr uint32_t kWorkParam = 0, kWorkRaw = 1;
+constexpr uint32_t kParamTileElems = 1u << 16;
+constexpr uint32_t kRawTileBytes = 1u << 18;
+
+// Work list of the fused step over the whole layout (needs L.adam_ok).
+void build_work_tiles(const Layout& L, std::vector<WorkTile>& out);
+
 // Returns FF_OK or a negative ff_status; `out` is valid only on FF_OK.
 // tile_log2: 0 = default tile size, else log2 of the tile size in bytes (clamped to
 // [10, log2(chunk_bytes)]).

@@ -168,3 +168,143 @@ def test_pack_on_a_side_stream(oracle):
     want_buf, want_crcs = oracle.pack(_host_segments(shard)[0], shard.chunk_bytes)
     assert np.array_equal(chunks.cpu().numpy(), want_buf)
     assert np.array_equal(_u32(crcs), want_crcs) and int(n_bad.item()) == 0
+
+
+# ---- fused AdamW step + snapshot -----------------------------------------------------------------
+
+HP = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1000)
+
+
+def _adam_and_compare(oracle, numels, chunk, seed, hp=HP, extra_raw=None):
+    """Runs ff_adam_step_snapshot and the oracle's unfused definition (update, then pack) on the
+    same inputs.  fp32 state: max relative error <= 1e-6 is the acceptance bound; the fixed
+    operation order makes the two bit-identical, which is what is asserted.  bf16 weights: exact
+    rounding of the GPU's own fp32 master.  Snapshot bytes and CRCs: bit-exact."""
+    shard = wl.param_shard("a", numels, chunk, seed, DEV, with_grads=True)
+    tensors = list(shard.segments)
+    kinds, pids = [], []
+    for pid in range(len(shard.params)):
+        kinds += [ff.FF_KIND_W16, ff.FF_KIND_MASTER, ff.FF_KIND_M, ff.FF_KIND_V]
+        pids += [pid] * 4
+    if extra_raw is not None:
+        for pos, t in extra_raw:
+            tensors.insert(pos, t)
+            kinds.insert(pos, ff.FF_KIND_RAW)
+            pids.insert(pos, 0)
+    plan = ff.ff_snapshot_plan(tensors, chunk, kinds=kinds, param_ids=pids)
+    assert plan.num_params == len(numels)
+    # host copies for the oracle, taken before the in-place update
+    host = [wl.to_numpy_bytes(t) for t in tensors]
+    views = {id(t): h for t, h in zip(tensors, host)}
+    params_np, grads_np = [], []
+    for p in shard.params:
+        params_np.append((views[id(p.w16)].view(np.uint16), views[id(p.master)].view(np.float32),
+                          views[id(p.m)].view(np.float32), views[id(p.v)].view(np.float32)))
+        grads_np.append(wl.to_numpy_bytes(p.grad).view(np.uint16))
+    chunks, crcs, bad, n_bad = ff.alloc_outputs(plan, DEV)
+    chunks.fill_(0xA5)
+    crcs.fill_(-1)
+    ff.ff_adam_step_snapshot(plan, [p.grad for p in shard.params], hp, chunks, crcs)
+    torch.cuda.synchronize()
+    want_buf, want_crcs = oracle.adam_snapshot(params_np, grads_np, host, chunk, hp, threads=8)
+    for p, (w16, master, m, v) in zip(shard.params, params_np):
+        for name, got_t, want in (("master", p.master, master), ("m", p.m, m), ("v", p.v, v)):
+            got = got_t.cpu().numpy()
+            rel = np.abs(got.astype(np.float64) - want) / np.maximum(np.abs(want), 1.1754944e-38)
+            assert rel.max(initial=0.0) <= 1e-6, name
+            assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), name
+        # bf16 weight: exact RNE of the GPU's own fp32 master
+        got_w = wl.to_numpy_bytes(p.w16).view(np.uint16)
+        assert np.array_equal(got_w, wl.to_numpy_bytes(p.master.to(torch.bfloat16)).view(np.uint16))
+        assert np.array_equal(got_w, w16)
+    assert np.array_equal(chunks.cpu().numpy(), want_buf)
+    assert np.array_equal(_u32(crcs), want_crcs)
+    # fused == unfused: ff_pack of the in-place result gives the same snapshot
+    chunks2, crcs2, _, _ = ff.alloc_outputs(plan, DEV)
+    ff.ff_pack(plan, chunks2, crcs2)
+    torch.cuda.synchronize()
+    assert torch.equal(chunks, chunks2) and torch.equal(crcs, crcs2)
+    return shard, plan
+
+
+@pytest.mark.parametrize("chunk", [1024, 4096, 1 << 16, 1 << 20])
+def test_fused_adam_small_ragged(oracle, chunk):
+    # odd element counts put fp32 segments at stream offsets 2 mod 4, so elements straddle
+    # chunk boundaries; counts below and above one 256-element row and one 65536-element tile
+    numels = [1, 3, 255, 256, 257, 1000, 4097, 70001, 131072, 65536 + 255, 5, 77]
+    _adam_and_compare(oracle, numels, chunk, seed=chunk)
+
+
+def test_fused_adam_many_random_sizes(oracle):
+    numels = [int(x) for x in np.random.default_rng(42).integers(1, 30000, size=60)]
+    _adam_and_compare(oracle, numels, 8192, seed=42)
+
+
+@pytest.mark.parametrize("step", [1, 2, 1000])
+def test_fused_adam_steps_and_hparams(oracle, step):
+    hp = dict(lr=1e-3, beta1=0.8, beta2=0.999, eps=1e-6, weight_decay=0.0, step=step)
+    _adam_and_compare(oracle, [5000, 12345, 300], 4096, seed=step, hp=hp)
+
+
+def test_fused_adam_with_raw_segments(oracle):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(3)
+    raw1 = torch.randn(3001, device=DEV, generator=g)
+    raw2 = torch.randn(70000, device=DEV, generator=g).to(torch.bfloat16)
+    raw3 = torch.randn(9, device=DEV, generator=g).to(torch.bfloat16)
+    _adam_and_compare(oracle, [1000, 33333, 77], 4096, seed=9,
+                      extra_raw=[(0, raw1), (5, raw2), (14, raw3)])
+
+
+def test_fused_adam_special_values(oracle):
+    # zeros, denormals, infinities and NaNs in the state flow through identically
+    shard = wl.param_shard("a", [4096], 4096, 5, DEV, with_grads=True)
+    p = shard.params[0]
+    p.v[:8] = torch.tensor([0.0, 1e-45, 1e-40, 1e-38, float("inf"), 0.0, 1e-30, 4.0], device=DEV)
+    p.m[:8] = torch.tensor([0.0, 1e-45, -1e-40, float("nan"), 1.0, float("inf"), -0.0, 1e-20], device=DEV)
+    p.master[8:12] = torch.tensor([float("nan"), float("inf"), -float("inf"), 3.4e38], device=DEV)
+    p.grad[12:16] = torch.tensor([0.0, -0.0, 1e-38, 65504.0], device=DEV).to(torch.bfloat16)
+    host = [wl.to_numpy_bytes(t) for t in shard.segments]
+    params_np = [(host[0].view(np.uint16), host[1].view(np.float32), host[2].view(np.float32),
+                  host[3].view(np.float32))]
+    grads_np = [wl.to_numpy_bytes(p.grad).view(np.uint16)]
+    plan = ff.plan_for_shard(shard)
+    chunks, crcs, _, _ = ff.alloc_outputs(plan, DEV)
+    ff.ff_adam_step_snapshot(plan, [p.grad], HP, chunks, crcs)
+    torch.cuda.synchronize()
+    oracle.adam_snapshot(params_np, grads_np, host, 4096, HP)
+    # A NaN result is correct whatever its sign and payload (IEEE 754 leaves both open, and the
+    # CPU's subtract and the GPU's add-of-negated differ in the sign they give): compare what is
+    # unique -- every non-NaN value bit for bit, and NaN-ness position by position.
+    n_nan = 0
+    for got_t, want, bits in ((p.w16, params_np[0][0], 16), (p.master, params_np[0][1], 32),
+                              (p.m, params_np[0][2], 32), (p.v, params_np[0][3], 32)):
+        got = wl.to_numpy_bytes(got_t).view(np.uint16 if bits == 16 else np.uint32)
+        want = want.view(got.dtype)
+        emask, fmask = (0x7F80, 0x007F) if bits == 16 else (0x7F800000, 0x007FFFFF)
+        nan_g = ((got & emask) == emask) & ((got & fmask) != 0)
+        nan_w = ((want & emask) == emask) & ((want & fmask) != 0)
+        assert np.array_equal(nan_g, nan_w)
+        n_nan += int(nan_w.sum())
+        assert np.array_equal(got[~nan_w], want[~nan_w])
+    assert n_nan >= 3
+    # and the snapshot is the packed image of the state the GPU left in place
+    chunks2, crcs2, _, _ = ff.alloc_outputs(plan, DEV)
+    ff.ff_pack(plan, chunks2, crcs2)
+    torch.cuda.synchronize()
+    assert torch.equal(chunks, chunks2) and torch.equal(crcs, crcs2)
+
+
+def test_fused_adam_argument_errors():
+    shard = wl.param_shard("a", [100], 1024, 5, DEV, with_grads=True)
+    p = shard.params[0]
+    plan = ff.plan_for_shard(shard)
+    chunks, crcs, _, _ = ff.alloc_outputs(plan, DEV)
+    with pytest.raises(ff.FFError) as e:
+        ff.ff_adam_step_snapshot(plan, [p.grad], dict(HP, step=0), chunks, crcs)
+    assert e.value.status == ff.FF_ERR_INVALID
+    # a plan without complete groups has nothing to step
+    raw = ff.ff_snapshot_plan([p.master, p.m], 1024)
+    with pytest.raises(ff.FFError) as e:
+        ff.ff_adam_step_snapshot(raw, [p.grad], HP, chunks, crcs)
+    assert e.value.status == ff.FF_ERR_INVALID

@@ -131,6 +131,8 @@ def test_fold_relations_are_multiples_of_the_generator(oracle):
             acc = oracle.crc_shift(0x80000000, 4 * (S * NE + f))
             assert len(tabs["TAP_E"][f]) == NT
             for e, c in zip(tabs["TAP_E"][f], tabs["TAP_F"][f]):
+                if (e, c) == (255, 255):      # unused slot
+                    continue
                 assert 0 <= e < NE and 0 <= c < NF
                 acc ^= oracle.crc_shift(0x80000000, 4 * (S * e + c))
             assert acc == 0
