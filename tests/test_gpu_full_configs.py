@@ -1,0 +1,182 @@
+"""GPU parity at the full sizes of the five configurations, in the launch configuration the bench
+times.  Where the whole result is too large for the CPU oracle, sampled chunks are compared with
+the oracle one by one and size-independent properties (round trip, fused == unfused, exact
+corruption set) cover the rest."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_03644_amd import binding as ff
+from paper_2512_03644_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def _stream_slices(plan, tensors, lo, hi):
+    """Host copies of the pieces of the segments that cover stream range [lo, hi)."""
+    out = []
+    for i, t in enumerate(tensors):
+        b, e = plan.segment_range(i)
+        if e <= lo or b >= hi:
+            continue
+        raw = t.view(torch.uint8)
+        out.append(raw[max(lo, b) - b:min(hi, e) - b].cpu().numpy())
+    return out
+
+
+def _check_sampled_chunks(oracle, plan, tensors, chunks, crcs, sample):
+    C = plan.chunk_bytes
+    crcs_h = _u32(crcs)
+    for j in sample:
+        pieces = _stream_slices(plan, tensors, j * C, (j + 1) * C)
+        want_buf, want_crc = oracle.pack(pieces, C)
+        assert want_buf.size == C
+        got = chunks[j * C:(j + 1) * C].cpu().numpy()
+        assert np.array_equal(got, want_buf), "chunk %d bytes" % j
+        assert int(crcs_h[j]) == int(want_crc[0]), "chunk %d crc" % j
+
+
+def _boundary_chunks(plan, n_segments, limit):
+    C = plan.chunk_bytes
+    out = []
+    for i in range(0, n_segments, max(1, n_segments // limit)):
+        b, _ = plan.segment_range(i)
+        out.append(b // C)
+    return out
+
+
+def _sample(plan, n_segments, rng, k=24):
+    n = plan.num_chunks
+    s = {0, 1, n - 2, n - 1} | {int(x) for x in rng.integers(0, n, size=k)}
+    s |= set(_boundary_chunks(plan, n_segments, 12))
+    return sorted(x for x in s if 0 <= x < n)
+
+
+def test_config2_llama7b_pack_restore(oracle):
+    shard = wl.config_llama7b(DEV)
+    plan = ff.plan_for_shard(shard)
+    assert plan.payload_bytes == 11791761408 and plan.num_chunks == 2812
+    assert plan.num_segments == 904
+    chunks, crcs, bad, n_bad = ff.alloc_outputs(plan, DEV)
+    chunks.fill_(0xA5)
+    ff.ff_pack(plan, chunks, crcs)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(2)
+    _check_sampled_chunks(oracle, plan, shard.segments, chunks, crcs,
+                          _sample(plan, len(shard.segments), rng))
+    # zero tail of the last chunk
+    assert not bool(chunks[plan.payload_bytes:].any())
+    # round trip into poisoned tensors
+    saved = [t.clone() for t in shard.segments]
+    for t in shard.segments:
+        t.view(torch.uint8).fill_(0xA5)
+    ff.ff_restore(plan, chunks, crcs, bad, n_bad)
+    torch.cuda.synchronize()
+    assert int(n_bad.item()) == 0 and not bool(bad.any())
+    for t, s in zip(shard.segments, saved):
+        assert torch.equal(t.view(torch.uint8), s.view(torch.uint8))
+
+
+def test_config3_fragmented_full(oracle):
+    shard = wl.config_fragmented(DEV)
+    plan = ff.plan_for_shard(shard)
+    assert plan.num_segments == 20000
+    chunks, crcs, bad, n_bad = ff.alloc_outputs(plan, DEV)
+    chunks.fill_(0xA5)
+    ff.ff_pack(plan, chunks, crcs)
+    torch.cuda.synchronize()
+    arena = shard.arena.cpu().numpy()
+    host = [arena[o:o + n] for o, n in shard.spans]
+    want_buf, want_crcs = oracle.pack(host, shard.chunk_bytes, threads=16)
+    assert np.array_equal(_u32(crcs), want_crcs)
+    got = chunks.cpu().numpy()
+    assert np.array_equal(got, want_buf)
+    del got, want_buf
+    # restore into poisoned segments; the gaps of the arena must not change
+    before = shard.arena.clone()
+    for o, n in shard.spans:
+        shard.arena[o:o + n] = 0xA5
+    ff.ff_restore(plan, chunks, crcs, bad, n_bad)
+    torch.cuda.synchronize()
+    assert int(n_bad.item()) == 0
+    assert torch.equal(shard.arena, before)
+
+
+def test_config4_fused_adam_full(oracle):
+    shard = wl.config_llama7b(DEV, with_grads=True)
+    plan = ff.plan_for_shard(shard)
+    hp = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1000)
+    # oracle on a sample of parameter groups (host copies taken before the in-place update)
+    sample = [0, 1, 5, 7, 100, 224, 225]
+    host = {}
+    for i in sample:
+        p = shard.params[i]
+        host[i] = [wl.to_numpy_bytes(t) for t in (p.w16, p.master, p.m, p.v, p.grad)]
+    chunks, crcs, bad, n_bad = ff.alloc_outputs(plan, DEV)
+    chunks.fill_(0xA5)
+    ff.ff_adam_step_snapshot(plan, [p.grad for p in shard.params], hp, chunks, crcs)
+    torch.cuda.synchronize()
+    for i in sample:
+        w16, master, m, v, g = host[i]
+        oracle.adam_f32(g.view(np.uint16), master.view(np.float32), m.view(np.float32),
+                        v.view(np.float32), w16.view(np.uint16), **hp)
+        p = shard.params[i]
+        for got_t, want in ((p.w16, w16), (p.master, master), (p.m, m), (p.v, v)):
+            assert np.array_equal(wl.to_numpy_bytes(got_t), want), i
+        # max relative error bound of the acceptance criterion (implied by bit equality)
+        got = p.master.cpu().numpy().astype(np.float64)
+        ref = master.view(np.float32).astype(np.float64)
+        assert np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1.1754944e-38)) <= 1e-6
+    # bf16 weights are the exact rounding of the fp32 masters the GPU produced
+    for p in shard.params[::17]:
+        assert torch.equal(p.w16, p.master.to(torch.bfloat16))
+    # fused == unfused: packing the in-place result reproduces chunks and CRCs bit for bit
+    chunks2, crcs2, _, _ = ff.alloc_outputs(plan, DEV)
+    ff.ff_pack(plan, chunks2, crcs2)
+    torch.cuda.synchronize()
+    assert torch.equal(crcs, crcs2)
+    assert torch.equal(chunks, chunks2)
+    rng = np.random.default_rng(4)
+    _check_sampled_chunks(oracle, plan, shard.segments, chunks, crcs,
+                          _sample(plan, len(shard.segments), rng, k=8))
+
+
+def test_config5_llama70b_verified_restore(oracle):
+    shard = wl.config_llama70b(DEV)
+    plan = ff.plan_for_shard(shard)
+    assert plan.payload_bytes == 15433334784 and plan.num_chunks == 1840
+    assert plan.num_segments == 2248
+    C = plan.chunk_bytes
+    chunks, crcs, bad, n_bad = ff.alloc_outputs(plan, DEV)
+    ff.ff_pack(plan, chunks, crcs)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    _check_sampled_chunks(oracle, plan, shard.segments, chunks, crcs,
+                          _sample(plan, len(shard.segments), rng, k=6))
+    hits = wl.corrupt_chunks(plan.num_chunks, C)
+    assert len(hits) == 18
+    for c, off, bit in hits:
+        chunks[c * C + off] ^= (1 << bit)
+    saved = [t.clone() for t in shard.segments]
+    for t in shard.segments:
+        t.view(torch.uint8).fill_(0xA5)
+    ff.ff_restore(plan, chunks, crcs, bad, n_bad)
+    torch.cuda.synchronize()
+    assert int(n_bad.item()) == 18
+    assert sorted(torch.nonzero(bad).flatten().tolist()) == [c for c, _, _ in hits]
+    # the oracle agrees on a corrupted and a clean chunk
+    for j in (hits[0][0], (hits[0][0] + 1) % plan.num_chunks):
+        wb, wn = oracle.verify(chunks[j * C:(j + 1) * C].cpu().numpy(), _u32(crcs)[j:j + 1], C)
+        assert int(wb[0]) == int(bad[j].item())
+    # everything outside the flipped bits round-trips: exactly one differing byte per flip that
+    # fell into the payload
+    expected = sum(1 for c, off, _ in hits if c * C + off < plan.payload_bytes)
+    diff = 0
+    for t, s in zip(shard.segments, saved):
+        diff += int((t.view(torch.uint8) != s.view(torch.uint8)).sum().item())
+    assert diff == expected
