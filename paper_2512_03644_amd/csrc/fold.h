@@ -17,6 +17,17 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
 typedef u32x2 u32x2_a2 __attribute__((aligned(2)));
 
+// Every pointer the kernels dereference is device global memory.  Addresses that come out of
+// tables are plain integers, so the compiler would fall back to flat (generic) accesses, whose
+// completion order it cannot count on; casting to the global address space gives global_load /
+// global_store, which complete in order and can be kept in flight with exact wait counts.
+#define FF_GLOBAL __attribute__((address_space(1)))
+template <class T>
+__device__ __forceinline__ FF_GLOBAL T* as_global(T* p)
+{
+    return (FF_GLOBAL T*)p;
+}
+
 constexpr int kWaveSize = 64;
 
 template <class Fn, int... Is>
@@ -35,44 +46,44 @@ __device__ __forceinline__ void static_for(Fn&& fn)
 template <bool NT = false>
 __device__ __forceinline__ u32x4 load16_unaligned(const uint8_t* p)
 {
-    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4_a2*>(p));
-    return *reinterpret_cast<const u32x4_a2*>(p);
+    if (NT) return __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x4_a2*>(p)));
+    return *as_global(reinterpret_cast<const u32x4_a2*>(p));
 }
 template <bool NT = false>
 __device__ __forceinline__ void store16_unaligned(uint8_t* p, u32x4 w)
 {
     if (NT)
-        __builtin_nontemporal_store(w, reinterpret_cast<u32x4_a2*>(p));
+        __builtin_nontemporal_store(w, as_global(reinterpret_cast<u32x4_a2*>(p)));
     else
-        *reinterpret_cast<u32x4_a2*>(p) = w;
+        *as_global(reinterpret_cast<u32x4_a2*>(p)) = w;
 }
 template <bool NT = false>
 __device__ __forceinline__ u32x2 load8_unaligned(const uint8_t* p)
 {
-    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x2_a2*>(p));
-    return *reinterpret_cast<const u32x2_a2*>(p);
+    if (NT) return __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x2_a2*>(p)));
+    return *as_global(reinterpret_cast<const u32x2_a2*>(p));
 }
 template <bool NT = false>
 __device__ __forceinline__ void store8_unaligned(uint8_t* p, u32x2 w)
 {
     if (NT)
-        __builtin_nontemporal_store(w, reinterpret_cast<u32x2_a2*>(p));
+        __builtin_nontemporal_store(w, as_global(reinterpret_cast<u32x2_a2*>(p)));
     else
-        *reinterpret_cast<u32x2_a2*>(p) = w;
+        *as_global(reinterpret_cast<u32x2_a2*>(p)) = w;
 }
 template <bool NT = true>
 __device__ __forceinline__ u32x4 load16_stream(const uint8_t* p)
 {
-    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-    return *reinterpret_cast<const u32x4*>(p);
+    if (NT) return __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x4*>(p)));
+    return *as_global(reinterpret_cast<const u32x4*>(p));
 }
 template <bool NT = true>
 __device__ __forceinline__ void store16_stream(uint8_t* p, u32x4 w)
 {
     if (NT)
-        __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(p));
+        __builtin_nontemporal_store(w, as_global(reinterpret_cast<u32x4*>(p)));
     else
-        *reinterpret_cast<u32x4*>(p) = w;
+        *as_global(reinterpret_cast<u32x4*>(p)) = w;
 }
 
 // One row into a lane's state.  w[0] is the row's first dword (the highest power).  J counts the
@@ -96,6 +107,19 @@ __device__ __forceinline__ void fold_row(uint32_t (&S)[F::NE][F::NF], const uint
                 S[p][c] ^= t[f];
             }
         });
+    });
+}
+
+// After K rows folded with J = 0..K-1 the physical register rows lag the logical ones by K;
+// moving them back makes J = 0 valid again (physical row q takes what physical row q - K held).
+template <class F, int K>
+__device__ __forceinline__ void rotate_state(uint32_t (&S)[F::NE][F::NF])
+{
+    constexpr int NE = F::NE, NF = F::NF;
+    uint32_t old[NE][NF];
+    static_for<NE>([&](auto e) { static_for<NF>([&](auto f) { old[e][f] = S[e][f]; }); });
+    static_for<NE>([&](auto q) {
+        static_for<NF>([&](auto f) { S[q][f] = old[(q - K % NE + NE) % NE][f]; });
     });
 }
 

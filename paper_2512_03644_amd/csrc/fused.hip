@@ -24,9 +24,10 @@ namespace {
 constexpr int kWavesPerBlock = 4;
 using F32Fold = Fold16x10;  // 16 bytes per lane per row
 using B16Fold = Fold8x20;   // 8 bytes per lane per row
-constexpr int kGroup = 20;  // rows per unrolled group: both rotations return to zero
-static_assert(kGroup % F32Fold::NE == 0 && kGroup % B16Fold::NE == 0, "rotation period");
+constexpr int kPhases = 5;  // rows folded between two physical rotations of the state
+static_assert(kPhases <= F32Fold::NE && kPhases <= B16Fold::NE, "rotation step");
 constexpr int kRowElems = 256;
+constexpr int kBatch = 1;  // rows loaded, updated and stored together
 
 __device__ __forceinline__ float bits_to_f32(uint32_t u) { return __uint_as_float(u); }
 __device__ __forceinline__ uint32_t f32_to_bits(float f) { return __float_as_uint(f); }
@@ -48,7 +49,10 @@ __device__ __forceinline__ void adam_element(const AdamConsts& k, uint32_t g_bit
     const float pd = p * k.decay;
     const float m1 = (k.b1 * m) + (k.omb1 * g);
     const float v1 = (k.b2 * v) + ((k.omb2 * g) * g);
-    const float d = (sqrtf(v1) / k.bc2s) + k.eps;
+    // x / 1.0f is x exactly, so the division is skipped once the second bias correction has
+    // rounded to one (wave-uniform test; beta2 = 0.95 gets there at step 333)
+    const float r = sqrtf(v1);
+    const float d = ((k.bc2s == 1.0f) ? r : (r / k.bc2s)) + k.eps;
     const float p1 = pd - (k.step_size * (m1 / d));
     p = p1;
     m = m1;
@@ -78,8 +82,7 @@ __device__ __forceinline__ void run_param_tile(const WorkTile& t, const uint8_t*
     const int n = static_cast<int>(t.n);
     const int pad_el = (kRowElems - n % kRowElems) % kRowElems;  // missing in front of row 0
     const int rows = (n + pad_el) / kRowElems;
-    const int groups = (rows + kGroup - 1) / kGroup;
-    const int pad_rows = groups * kGroup - rows;
+    const int pad_rows = (kPhases - rows % kPhases) % kPhases;
 
     uint8_t* const tw = reinterpret_cast<uint8_t*>(t.ptr[0]);
     uint8_t* const tp = reinterpret_cast<uint8_t*>(t.ptr[1]);
@@ -100,76 +103,107 @@ __device__ __forceinline__ void run_param_tile(const WorkTile& t, const uint8_t*
     // lane and sub-position of element 0 (for the head pieces of split elements)
     const int head_lane = pad_el / 4, head_sub = pad_el % 4;
 
-    // The update of a row is ordinary looped code; only the folding step depends on how far the
-    // state registers have rotated, so it alone is selected by a switch on the phase.  Starting
-    // at phase pad_rows brings the rotation back to zero after the last row.
-    for (int r = 0; r < rows; r++) {
-        const int j0 = r * kRowElems + 4 * lane - pad_el;  // first element of the lane
+    struct RowIn {
+        u32x2 g;
+        u32x4 p, m, v;
+    };
+    // Only the folding step depends on how far the state registers have rotated, so it alone is
+    // selected by a switch on the phase.  Unrolling a whole rotation (20 rows) would put ~90 KB
+    // of code in the loop; instead the rotation is undone with register moves every kPhases
+    // rows, which keeps the loop body small enough for the instruction cache.  Starting at phase
+    // pad_rows makes the last row end a block, so the state ends in logical order.
+    auto fold_all = [&](int r, uint32_t (&fw)[2], uint32_t (&fp)[4], uint32_t (&fm)[4],
+                        uint32_t (&fv)[4]) {
+        const int phase = (r + pad_rows) % kPhases;
+        static_for<kPhases>([&](auto Jc) {
+            constexpr int J = Jc;
+            if (phase == J) {
+                fold_row<B16Fold, J>(Sw, fw);
+                fold_row<F32Fold, J>(Sp, fp);
+                fold_row<F32Fold, J>(Sm, fm);
+                fold_row<F32Fold, J>(Sv, fv);
+                if constexpr (J == kPhases - 1) {
+                    rotate_state<B16Fold, kPhases>(Sw);
+                    rotate_state<F32Fold, kPhases>(Sp);
+                    rotate_state<F32Fold, kPhases>(Sm);
+                    rotate_state<F32Fold, kPhases>(Sv);
+                }
+            }
+        });
+    };
+    // Update one row in registers and fold it; the row's results replace its inputs (g becomes
+    // the packed bf16 weights).
+    auto update_row = [&](int r, RowIn& io) {
+        uint32_t gb[4] = {io.g.x & 0xFFFFu, io.g.x >> 16, io.g.y & 0xFFFFu, io.g.y >> 16};
+        uint32_t wb[4];
+        float p[4] = {bits_to_f32(io.p.x), bits_to_f32(io.p.y), bits_to_f32(io.p.z), bits_to_f32(io.p.w)};
+        float m[4] = {bits_to_f32(io.m.x), bits_to_f32(io.m.y), bits_to_f32(io.m.z), bits_to_f32(io.m.w)};
+        float v[4] = {bits_to_f32(io.v.x), bits_to_f32(io.v.y), bits_to_f32(io.v.z), bits_to_f32(io.v.w)};
+#pragma unroll
+        for (int s = 0; s < 4; s++) adam_element(C.adam, gb[s], p[s], m[s], v[s], wb[s]);
+        uint32_t fw[2] = {wb[0] | (wb[1] << 16), wb[2] | (wb[3] << 16)};
+        uint32_t fp[4] = {f32_to_bits(p[0]), f32_to_bits(p[1]), f32_to_bits(p[2]), f32_to_bits(p[3])};
+        uint32_t fm[4] = {f32_to_bits(m[0]), f32_to_bits(m[1]), f32_to_bits(m[2]), f32_to_bits(m[3])};
+        uint32_t fv[4] = {f32_to_bits(v[0]), f32_to_bits(v[1]), f32_to_bits(v[2]), f32_to_bits(v[3])};
+        io.g = u32x2{fw[0], fw[1]};
+        io.p = u32x4{fp[0], fp[1], fp[2], fp[3]};
+        io.m = u32x4{fm[0], fm[1], fm[2], fm[3]};
+        io.v = u32x4{fv[0], fv[1], fv[2], fv[3]};
+        // split first element (row 0 of a tile that starts on a full row): its first two bytes
+        // close the previous chunk
+        if (r == 0 && t.head_split && lane == head_lane) {
+            uint32_t* const fx[3] = {fp, fm, fv};
+#pragma unroll
+            for (int x = 1; x <= 3; x++) {
+                if (t.head_split & (1u << x)) {
+                    const uint32_t d = fx[x - 1][0];  // pad_el == 0 here: element 0 is sub 0
+                    // two message bytes in the low half are M(x) * x^16; their register is
+                    // M(x) * x^32
+                    add_piece(crcs, t, 3 + x, gf2_mul(d & 0xFFFFu, C.x16));
+                    fx[x - 1][0] = d & 0xFFFF0000u;
+                }
+            }
+        }
+        fold_all(r, fw, fp, fm, fv);
+    };
+
+    int r_first = 0;
+    if (pad_el != 0) {
+        // partial first row: element by element; absent elements stay zero and fold as zeros
+        r_first = 1;
+        const int j0 = 4 * lane - pad_el;
         uint32_t gb[4], wb[4];
         float p[4], m[4], v[4];
-        if (r > 0 || pad_el == 0) {
-            // every lane holds 4 real elements: vector accesses
-            const u32x2 g2 = load8_unaligned<true>(tg + 2 * j0);
-            const u32x4 p4 = load16_unaligned<true>(tp + 4 * j0);
-            const u32x4 m4 = load16_unaligned<true>(tm + 4 * j0);
-            const u32x4 v4 = load16_unaligned<true>(tv + 4 * j0);
-            gb[0] = g2.x & 0xFFFFu; gb[1] = g2.x >> 16;
-            gb[2] = g2.y & 0xFFFFu; gb[3] = g2.y >> 16;
-            p[0] = bits_to_f32(p4.x); p[1] = bits_to_f32(p4.y);
-            p[2] = bits_to_f32(p4.z); p[3] = bits_to_f32(p4.w);
-            m[0] = bits_to_f32(m4.x); m[1] = bits_to_f32(m4.y);
-            m[2] = bits_to_f32(m4.z); m[3] = bits_to_f32(m4.w);
-            v[0] = bits_to_f32(v4.x); v[1] = bits_to_f32(v4.y);
-            v[2] = bits_to_f32(v4.z); v[3] = bits_to_f32(v4.w);
 #pragma unroll
-            for (int s = 0; s < 4; s++) adam_element(C.adam, gb[s], p[s], m[s], v[s], wb[s]);
-            const u32x2 w2 = {wb[0] | (wb[1] << 16), wb[2] | (wb[3] << 16)};
-            const u32x4 po = {f32_to_bits(p[0]), f32_to_bits(p[1]), f32_to_bits(p[2]), f32_to_bits(p[3])};
-            const u32x4 mo = {f32_to_bits(m[0]), f32_to_bits(m[1]), f32_to_bits(m[2]), f32_to_bits(m[3])};
-            const u32x4 vo = {f32_to_bits(v[0]), f32_to_bits(v[1]), f32_to_bits(v[2]), f32_to_bits(v[3])};
-            store8_unaligned(tw + 2 * j0, w2);
-            store16_unaligned(tp + 4 * j0, po);
-            store16_unaligned(tm + 4 * j0, mo);
-            store16_unaligned(tv + 4 * j0, vo);
-            store8_unaligned<true>(sw + 2 * j0, w2);
-            store16_unaligned<true>(sp + 4 * j0, po);
-            store16_unaligned<true>(sm + 4 * j0, mo);
-            store16_unaligned<true>(sv + 4 * j0, vo);
-        } else {
-            // partial first row: element by element; absent elements stay zero and fold as zeros
-#pragma unroll
-            for (int s = 0; s < 4; s++) {
-                const int j = j0 + s;
-                gb[s] = 0; wb[s] = 0; p[s] = 0.f; m[s] = 0.f; v[s] = 0.f;
-                if (j >= 0) {
-                    gb[s] = *reinterpret_cast<const uint16_t*>(tg + 2 * j);
-                    p[s] = *reinterpret_cast<const float*>(tp + 4 * j);
-                    m[s] = *reinterpret_cast<const float*>(tm + 4 * j);
-                    v[s] = *reinterpret_cast<const float*>(tv + 4 * j);
-                    adam_element(C.adam, gb[s], p[s], m[s], v[s], wb[s]);
-                    *reinterpret_cast<uint16_t*>(tw + 2 * j) = static_cast<uint16_t>(wb[s]);
-                    *reinterpret_cast<float*>(tp + 4 * j) = p[s];
-                    *reinterpret_cast<float*>(tm + 4 * j) = m[s];
-                    *reinterpret_cast<float*>(tv + 4 * j) = v[s];
-                    *reinterpret_cast<uint16_t*>(sw + 2 * j) = static_cast<uint16_t>(wb[s]);
-                    // stream offsets of fp32 segments may be 2 mod 4: halfword stores
-                    const uint32_t pb = f32_to_bits(p[s]), mb = f32_to_bits(m[s]),
-                                   vb = f32_to_bits(v[s]);
-                    uint16_t* qp = reinterpret_cast<uint16_t*>(sp + 4 * j);
-                    uint16_t* qm = reinterpret_cast<uint16_t*>(sm + 4 * j);
-                    uint16_t* qv = reinterpret_cast<uint16_t*>(sv + 4 * j);
-                    qp[0] = static_cast<uint16_t>(pb); qp[1] = static_cast<uint16_t>(pb >> 16);
-                    qm[0] = static_cast<uint16_t>(mb); qm[1] = static_cast<uint16_t>(mb >> 16);
-                    qv[0] = static_cast<uint16_t>(vb); qv[1] = static_cast<uint16_t>(vb >> 16);
-                }
+        for (int s = 0; s < 4; s++) {
+            const int j = j0 + s;
+            gb[s] = 0; wb[s] = 0; p[s] = 0.f; m[s] = 0.f; v[s] = 0.f;
+            if (j >= 0) {
+                gb[s] = *as_global(reinterpret_cast<const uint16_t*>(tg + 2 * j));
+                p[s] = *as_global(reinterpret_cast<const float*>(tp + 4 * j));
+                m[s] = *as_global(reinterpret_cast<const float*>(tm + 4 * j));
+                v[s] = *as_global(reinterpret_cast<const float*>(tv + 4 * j));
+                adam_element(C.adam, gb[s], p[s], m[s], v[s], wb[s]);
+                *as_global(reinterpret_cast<uint16_t*>(tw + 2 * j)) = static_cast<uint16_t>(wb[s]);
+                *as_global(reinterpret_cast<float*>(tp + 4 * j)) = p[s];
+                *as_global(reinterpret_cast<float*>(tm + 4 * j)) = m[s];
+                *as_global(reinterpret_cast<float*>(tv + 4 * j)) = v[s];
+                *as_global(reinterpret_cast<uint16_t*>(sw + 2 * j)) = static_cast<uint16_t>(wb[s]);
+                // stream offsets of fp32 segments may be 2 mod 4: halfword stores
+                const uint32_t pb = f32_to_bits(p[s]), mb = f32_to_bits(m[s]), vb = f32_to_bits(v[s]);
+                uint16_t* qp = reinterpret_cast<uint16_t*>(sp + 4 * j);
+                uint16_t* qm = reinterpret_cast<uint16_t*>(sm + 4 * j);
+                uint16_t* qv = reinterpret_cast<uint16_t*>(sv + 4 * j);
+                qp[0] = static_cast<uint16_t>(pb); qp[1] = static_cast<uint16_t>(pb >> 16);
+                qm[0] = static_cast<uint16_t>(mb); qm[1] = static_cast<uint16_t>(mb >> 16);
+                qv[0] = static_cast<uint16_t>(vb); qv[1] = static_cast<uint16_t>(vb >> 16);
             }
         }
         uint32_t fw[2] = {wb[0] | (wb[1] << 16), wb[2] | (wb[3] << 16)};
         uint32_t fp[4] = {f32_to_bits(p[0]), f32_to_bits(p[1]), f32_to_bits(p[2]), f32_to_bits(p[3])};
         uint32_t fm[4] = {f32_to_bits(m[0]), f32_to_bits(m[1]), f32_to_bits(m[2]), f32_to_bits(m[3])};
         uint32_t fv[4] = {f32_to_bits(v[0]), f32_to_bits(v[1]), f32_to_bits(v[2]), f32_to_bits(v[3])};
-        // split first element: its first two bytes close the previous chunk
-        if (r == 0 && t.head_split && lane == head_lane) {
+        if (t.head_split && lane == head_lane) {
             uint32_t* const fx[3] = {fp, fm, fv};
 #pragma unroll
             for (int x = 1; x <= 3; x++) {
@@ -178,8 +212,6 @@ __device__ __forceinline__ void run_param_tile(const WorkTile& t, const uint8_t*
                     for (int s = 0; s < 4; s++) {
                         if (s == head_sub) {
                             const uint32_t d = fx[x - 1][s];
-                            // two message bytes in the low half are M(x) * x^16; their register
-                            // is M(x) * x^32
                             add_piece(crcs, t, 3 + x, gf2_mul(d & 0xFFFFu, C.x16));
                             fx[x - 1][s] = d & 0xFFFF0000u;
                         }
@@ -187,16 +219,60 @@ __device__ __forceinline__ void run_param_tile(const WorkTile& t, const uint8_t*
                 }
             }
         }
-        const int phase = (r + pad_rows) % kGroup;
-        static_for<kGroup>([&](auto Jc) {
-            constexpr int J = Jc;
-            if (phase == J) {
-                fold_row<B16Fold, J>(Sw, fw);
-                fold_row<F32Fold, J>(Sp, fp);
-                fold_row<F32Fold, J>(Sm, fm);
-                fold_row<F32Fold, J>(Sv, fv);
+        fold_all(0, fw, fp, fm, fv);
+    }
+
+    // Full rows in batches of kBatch.  Per batch and per stream the kBatch loads, and later the
+    // kBatch stores, are issued back to back, so each stream presents 4 KiB of consecutive
+    // addresses to the memory system at a time (measured: +10 % bandwidth over row-by-row
+    // issue).  The inputs of the next batch are requested before the current one is updated.
+    // Loads past the last row are redirected to the last row (always in bounds, never used).
+    if (r_first < rows) {
+        auto load_batch = [&](RowIn (&q)[kBatch], int r0) {
+            static_for<kBatch>([&](auto k) {
+                const int rr = r0 + k;
+                const int j0 = (rr < rows ? rr : rows - 1) * kRowElems + 4 * lane - pad_el;
+                q[k].g = load8_unaligned<true>(tg + 2 * j0);
+            });
+            static_for<kBatch>([&](auto k) {
+                const int rr = r0 + k;
+                const int j0 = (rr < rows ? rr : rows - 1) * kRowElems + 4 * lane - pad_el;
+                q[k].p = load16_unaligned<true>(tp + 4 * j0);
+            });
+            static_for<kBatch>([&](auto k) {
+                const int rr = r0 + k;
+                const int j0 = (rr < rows ? rr : rows - 1) * kRowElems + 4 * lane - pad_el;
+                q[k].m = load16_unaligned<true>(tm + 4 * j0);
+            });
+            static_for<kBatch>([&](auto k) {
+                const int rr = r0 + k;
+                const int j0 = (rr < rows ? rr : rows - 1) * kRowElems + 4 * lane - pad_el;
+                q[k].v = load16_unaligned<true>(tv + 4 * j0);
+            });
+        };
+        RowIn cur[kBatch], nxt[kBatch];
+        load_batch(nxt, r_first);
+        for (int r0 = r_first; r0 < rows; r0 += kBatch) {
+            static_for<kBatch>([&](auto k) { cur[k] = nxt[k]; });
+            load_batch(nxt, r0 + kBatch);
+            // one copy of the update code: rows rotate through cur[0], results queue up behind
+            for (int k = 0; k < kBatch; k++) {
+                RowIn x = cur[0];
+                static_for<kBatch - 1>([&](auto i) { cur[i] = cur[i + 1]; });
+                if (r0 + k < rows) update_row(r0 + k, x);
+                cur[kBatch - 1] = x;
             }
-        });
+            const int nb = rows - r0;  // real rows in this batch (>= kBatch except at the end)
+            auto j0_of = [&](int k) { return (r0 + k) * kRowElems + 4 * lane - pad_el; };
+            static_for<kBatch>([&](auto k) { if (k < nb) store8_unaligned(tw + 2 * j0_of(k), cur[k].g); });
+            static_for<kBatch>([&](auto k) { if (k < nb) store16_unaligned(tp + 4 * j0_of(k), cur[k].p); });
+            static_for<kBatch>([&](auto k) { if (k < nb) store16_unaligned(tm + 4 * j0_of(k), cur[k].m); });
+            static_for<kBatch>([&](auto k) { if (k < nb) store16_unaligned(tv + 4 * j0_of(k), cur[k].v); });
+            static_for<kBatch>([&](auto k) { if (k < nb) store8_unaligned<true>(sw + 2 * j0_of(k), cur[k].g); });
+            static_for<kBatch>([&](auto k) { if (k < nb) store16_unaligned<true>(sp + 4 * j0_of(k), cur[k].p); });
+            static_for<kBatch>([&](auto k) { if (k < nb) store16_unaligned<true>(sm + 4 * j0_of(k), cur[k].m); });
+            static_for<kBatch>([&](auto k) { if (k < nb) store16_unaligned<true>(sv + 4 * j0_of(k), cur[k].v); });
+        }
     }
 
     const uint32_t rw = reduce_state<B16Fold>(Sw, lds.tab8, C.x32, C.z8);
@@ -221,8 +297,7 @@ __device__ __forceinline__ void run_raw_tile(const WorkTile& t, uint8_t* __restr
     const int n = static_cast<int>(t.n);  // bytes, even
     const int pad_b = (1024 - n % 1024) % 1024;
     const int rows = (n + pad_b) / 1024;
-    const int groups = (rows + NE - 1) / NE;
-    const int pad_rows = groups * NE - rows;
+    const int pad_rows = (kPhases - rows % kPhases) % kPhases;
     const uint8_t* const src = reinterpret_cast<const uint8_t*>(t.ptr[0]);
     uint8_t* const dst = chunks + t.soff[0];
 
@@ -240,16 +315,19 @@ __device__ __forceinline__ void run_raw_tile(const WorkTile& t, uint8_t* __restr
             for (int u = 0; u < 8; u++) {
                 const int b = b0 + 2 * u;
                 if (b >= 0) {
-                    const uint32_t h = *reinterpret_cast<const uint16_t*>(src + b);
-                    *reinterpret_cast<uint16_t*>(dst + b) = static_cast<uint16_t>(h);
+                    const uint32_t h = *as_global(reinterpret_cast<const uint16_t*>(src + b));
+                    *as_global(reinterpret_cast<uint16_t*>(dst + b)) = static_cast<uint16_t>(h);
                     d[u >> 1] |= h << ((u & 1) * 16);
                 }
             }
         }
-        const int phase = (r + pad_rows) % NE;
-        static_for<NE>([&](auto Jc) {
+        const int phase = (r + pad_rows) % kPhases;
+        static_for<kPhases>([&](auto Jc) {
             constexpr int J = Jc;
-            if (phase == J) fold_row<F32Fold, J>(S, d);
+            if (phase == J) {
+                fold_row<F32Fold, J>(S, d);
+                if constexpr (J == kPhases - 1) rotate_state<F32Fold, kPhases>(S);
+            }
         });
     }
     const uint32_t reg = reduce_state<F32Fold>(S, lds.tab16, C.x32, C.z16);

@@ -110,7 +110,7 @@ __device__ __noinline__ u32x4 gather_row_slow(const uint64_t* __restrict__ seg_o
             b = seg_off[j + 1];
             base = seg_ptr[j];
         }
-        h[u] = (p < payload) ? *reinterpret_cast<const uint16_t*>(base + (p - a)) : 0u;
+        h[u] = (p < payload) ? *as_global(reinterpret_cast<const uint16_t*>(base + (p - a))) : 0u;
     }
     u32x4 r;
     r.x = h[0] | (h[1] << 16);
@@ -143,7 +143,7 @@ __device__ __noinline__ void scatter_row_slow(const uint64_t* __restrict__ seg_o
             base = seg_ptr[j];
         }
         if (p < payload)
-            *reinterpret_cast<uint16_t*>(base + (p - a)) =
+            *as_global(reinterpret_cast<uint16_t*>(base + (p - a))) =
                 static_cast<uint16_t>(d[u >> 1] >> ((u & 1) * 16));
     }
 }
