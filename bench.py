@@ -8,12 +8,14 @@ plus fp32 master/m/v, 11.79 GB in 904 tensors, 4 MiB chunks (2812 chunks).
 
 Prints ONE JSON line.  `value` is the algorithmic HBM traffic of a step divided by its time
 (pack and restore each read and write every payload byte once: 2 B per payload byte; the fused
-Adam step moves 42 B per parameter).  `roofline` is the dominant kernel (the pack tile kernel):
+Adam step moves 42 B per parameter).  `roofline` is the longest-running kernel of the step:
 algorithmic bytes per launch over its HIP-event duration against the 8 TB/s HBM peak.
 `cpu_baseline` is the plain CPU oracle timed on this machine's host cores on a bounded sample of the
 same shard.
 """
 import argparse
+import glob
+import hashlib
 import json
 import os
 import sys
@@ -23,6 +25,29 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+
+
+def kernel_source_hash():
+    """sha256 over the library's sources: identifies the kernels a counter run belongs to."""
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2512_03644_amd", "csrc", "*"))):
+        if f.endswith((".hip", ".h", ".hpp", ".cpp")):
+            h.update(os.path.basename(f).encode())
+            h.update(open(f, "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter runs
+    (profiles/hbm_traffic.json), or None if the sources have changed since they were taken."""
+    try:
+        rec = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic.json")))
+    except (OSError, ValueError):
+        return None
+    if rec.get("source_sha256") != kernel_source_hash():
+        return None
+    k = rec.get("kernels", {}).get(kernel)
+    return None if k is None else k["hbm_bytes_per_launch"]
 
 
 def parse():
@@ -48,29 +73,46 @@ def event_ms(fn, n, torch):
     return [a.elapsed_time(b) for a, b in evs]
 
 
-def cpu_baseline(shard, n_params, torch):
-    """The oracle's pack + restore on the first n_params parameter groups of the shard."""
+def cpu_baseline(shard, n_params, hp, with_adam, torch):
+    """The oracle's step (AdamW update, pack, restore) on the first n_params parameter groups of
+    the shard, chunk ranges and parameters spread over the host cores by a thread pool."""
+    from concurrent.futures import ThreadPoolExecutor
     import numpy as np
     import oracle
     from paper_2512_03644_amd import workloads as wl
-    segs = [wl.to_numpy_bytes(t) for p in shard.params[:n_params]
-            for t in (p.w16, p.master, p.m, p.v)]
+    groups = [[wl.to_numpy_bytes(t) for t in (p.w16, p.master, p.m, p.v)]
+              for p in shard.params[:n_params]]
+    grads = [wl.to_numpy_bytes(p.grad).view(np.uint16) for p in shard.params[:n_params]] \
+        if with_adam else None
+    segs = [a for g in groups for a in g]
     nbytes = sum(s.size for s in segs)
+    n_el = sum(g[1].size // 4 for g in groups)
     cores = min(16, len(os.sched_getaffinity(0)))
     oracle.lib()
     t0 = time.perf_counter()
-    buf, crcs = oracle.pack(segs, shard.chunk_bytes, threads=cores)
+    if with_adam:
+        def upd(i):
+            w16, master, m, v = groups[i]
+            oracle.adam_f32(grads[i], master.view(np.float32), m.view(np.float32),
+                            v.view(np.float32), w16.view(np.uint16), **hp)
+        with ThreadPoolExecutor(cores) as ex:
+            list(ex.map(upd, range(len(groups))))
+        buf, crcs = oracle.pack(segs, shard.chunk_bytes, threads=cores)   # snapshot of the update
     t1 = time.perf_counter()
+    buf, crcs = oracle.pack(segs, shard.chunk_bytes, threads=cores)
+    t2 = time.perf_counter()
     dst = [np.empty_like(s) for s in segs]
     bad, n_bad = oracle.restore(dst, shard.chunk_bytes, buf, crcs, threads=cores)
-    t2 = time.perf_counter()
+    t3 = time.perf_counter()
     assert n_bad == 0
-    return {"value": round(4 * nbytes / (t2 - t0) / 1e9, 3), "unit": "GB/s", "cores": cores,
+    step_bytes = 4 * nbytes + (42 * n_el if with_adam else 0)
+    return {"value": round(step_bytes / (t3 - t0) / 1e9, 3), "unit": "GB/s", "cores": cores,
             "kind": "oracle",
-            "sample": "first %d of %d parameter groups of the same shard (%.2f GB payload), "
-                      "oracle pack then restore, traffic counted as on the GPU (2 B per payload "
-                      "byte per pass); pack %.2f s, restore %.2f s wall"
-                      % (n_params, len(shard.params), nbytes / 1e9, t1 - t0, t2 - t1)}
+            "sample": "first %d of %d parameter groups of the same shard (%.2f GB payload): oracle "
+                      "%spack, restore; bytes counted as for the GPU step; wall %.2f + %.2f + "
+                      "%.2f s" % (n_params, len(shard.params), nbytes / 1e9,
+                                  "AdamW update + pack (unfused), " if with_adam else "",
+                                  t1 - t0, t2 - t1, t3 - t2)}
 
 
 def main():
@@ -127,42 +169,54 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    # timed region: K steps; every op is bracketed by HIP events on the stream it is launched on
+    evs = {name: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                  for _ in range(args.steps)] for name, _, _ in ops}
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
+    for i in range(args.steps):
+        for name, fn, _ in ops:
+            a, b = evs[name][i]
+            a.record()
+            fn()
+            b.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     assert int(n_bad.item()) == 0
     ms_per_step = wall / args.steps * 1e3
 
-    # per-op durations (HIP events on the launch stream), and the copy ceiling beside them
     detail = {}
     for name, fn, nbytes in ops:
-        ts = event_ms(fn, max(args.steps, 5), torch)
+        ts = [a.elapsed_time(b) for a, b in evs[name]]
         avg = sum(ts) / len(ts)
         detail[name] = {"avg_ms": round(avg, 4), "min_ms": round(min(ts), 4),
                         "traffic_GBps": round(nbytes / avg / 1e6, 1),
                         "frac_of_peak": round(nbytes / avg / 1e6 / HBM_PEAK_GBS, 4)}
     detail["pack"]["payload_GBps"] = round(N / detail["pack"]["avg_ms"] / 1e6, 1)
     detail["restore"]["payload_GBps"] = round(N / detail["restore"]["avg_ms"] / 1e6, 1)
+    # the plain-copy ceiling of the same byte count, printed beside the real kernels
     src = torch.empty(N, dtype=torch.uint8, device=dev)
     ts = event_ms(lambda: ff.ff_copy_ceiling(chunks, src, N), 5, torch)
     copy_gbs = 2 * N / (sum(ts) / len(ts)) / 1e6
     del src
 
-    pack_ms = detail["pack"]["avg_ms"]
-    achieved = 2 * N / pack_ms / 1e6
-    roofline = {"bound": "hbm", "kernel": "tile_kernel<pack>", "achieved": round(achieved, 1),
+    # roofline of the dominant (longest-running) kernel of the step
+    kernels = {"adam_snapshot": ("fused_kernel", 42 * n_el), "pack": ("tile_kernel<pack>", 2 * N),
+               "restore": ("tile_kernel<restore>", 2 * N)}
+    dom = max(detail, key=lambda k: detail[k]["avg_ms"])
+    kname, kbytes = kernels[dom]
+    achieved = kbytes / detail[dom]["avg_ms"] / 1e6
+    roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": None,
-                "copy_ceiling_GBps": round(copy_gbs, 1),
-                "frac_of_copy_ceiling": round(achieved / copy_gbs, 4)}
+                "traffic": measured_traffic(kname),
+                "algorithmic_bytes_per_launch": kbytes,
+                "avg_launch_ms": detail[dom]["avg_ms"],
+                "copy_ceiling_GBps": round(copy_gbs, 1)}
 
     out = {"metric": "snapshot pack+CRC and restore GB/s, % of HBM peak, 7B-shaped shard",
            "value": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-           "vs_baseline": None, "dtype": "u8" if not with_adam else "u8+f32", "data": "synthetic",
+           "vs_baseline": None, "dtype": "f32" if with_adam else "u8", "data": "synthetic",
            "config": {"workload": "llama7b-dp8 shard: 226 params, bf16 w + fp32 master/m/v, "
                                   "%d B payload, 904 segments, 4 MiB chunks (%d)"
                                   % (N, plan.num_chunks),
@@ -171,7 +225,7 @@ def main():
            "pct_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS * 100, 2),
            "ops": detail, "roofline": roofline}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(shard, 32, torch)
+        out["cpu_baseline"] = cpu_baseline(shard, 48, hp, with_adam, torch)
     print(json.dumps(out))
 
 
