@@ -26,9 +26,9 @@
  *     enqueued on it and the call returns without synchronising; results stay on the device.
  *   - Return value: FF_OK (0) or a negative ff_status.  Nothing throws, nothing aborts.
  *     Corruption found by ff_restore is reported through bad[] / n_bad, never as an error code.
- *   - A plan is immutable.  Calls that use the same plan may run concurrently on different
- *     streams only if they also use different plans' scratch, i.e. they may NOT: a plan carries
- *     one scratch array of per-tile partial CRCs, so concurrent calls need one plan each.
+ *   - A plan's layout is immutable, but the plan carries one scratch array (a partial CRC per
+ *     tile, the gradient-pointer table of the fused step): two calls on the same plan must not
+ *     overlap in time.  Use one plan per concurrent stream.
  *   - Segments must not overlap each other, the chunk buffer or the crc arrays.
  */
 #ifndef FFSNAP_H
@@ -147,7 +147,7 @@ typedef struct {
  * weights are overwritten in place and the same bytes are written at their stream offsets in
  * `chunks`; RAW segments are copied unchanged; crcs as in ff_pack.  The result equals ff_pack
  * run after an unfused update.  grads: HOST array of ff_plan_num_params() DEVICE pointers to
- * bf16 gradients (4-byte aligned), indexed by param_id rank (ascending param_id); read only.
+ * bf16 gradients (2-byte aligned), indexed by param_id rank (ascending param_id); read only.
  * FF_ERR_INVALID if the plan has an incomplete group, mismatched element counts, or step == 0.
  */
 int ff_adam_step_snapshot(const ff_plan *plan, const void *const *grads, const ff_adam_hparams *hp,

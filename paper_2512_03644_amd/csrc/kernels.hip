@@ -11,8 +11,8 @@
 // CRC32C without table lookups in the inner loop.  A lane sees 4 dwords per row, 256 dwords
 // apart from row to row.  It keeps NE*4 dwords of state that represent its part of the message
 // as a polynomial in y = x^32; every row multiplies the state by y^256 (a rotation of register
-// names) and the 4 dwords that leave the top are XORed into 7 tap positions each, using sparse
-// multiples of the CRC generator (fold_taps.h).  That is 28 XORs per 16 bytes and is exact
+// names) and the 4 dwords that leave the top are XORed into 9 tap positions each, using sparse
+// multiples of the CRC generator (fold_taps.h).  That is 36 XORs per 16 bytes and is exact
 // GF(2) algebra.  Only at the end of a tile are the NE*4 dwords of every lane reduced to one
 // 32-bit register: Horner steps with byte tables (multiply by x^8192) held in LDS, then
 // bitwise multiplications to merge columns and lanes.  A second, tiny kernel merges the tile
