@@ -31,7 +31,7 @@ using Fold = Fold16x16;
 constexpr int kRowBytes = Fold::ROW_BYTES;
 constexpr int kNE = Fold::NE;
 constexpr int kNF = Fold::NF;
-constexpr int kDepth = 16;  // rows in flight per wavefront
+constexpr int kDepth = 8;  // rows in flight per wavefront
 static_assert(kNE % kDepth == 0, "queue slots must repeat with the state rotation");
 static_assert(kNF == 4 && kRowBytes == 1024, "one 16-byte word per lane per row");
 

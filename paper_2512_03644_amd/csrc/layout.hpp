@@ -67,6 +67,6 @@ void build_work_tiles(const Layout& L, std::vector<WorkTile>& out);
 int build_layout(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_bytes, unsigned tile_log2,
                  Layout& out);
 
-constexpr uint64_t kDefaultTileBytes = 1ull << 20;
+constexpr uint64_t kDefaultTileBytes = 1ull << 18;
 
 }  // namespace ffsnap
