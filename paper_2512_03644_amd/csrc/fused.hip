@@ -1,18 +1,18 @@
 // Fused optimizer step + snapshot for gfx950.
 //
-// One wavefront owns one work tile (layout.hpp): a run of up to 65536 elements of one parameter
+// A workgroup owns one work tile (layout.hpp): a run of up to 65536 elements of one parameter
 // group, or a run of bytes of a RAW segment.  A parameter tile is walked in rows of 256
 // elements, lane l taking 4 consecutive elements: 8 bytes of bf16 gradient and 3 x 16 bytes of
 // fp32 master/m/v come in, the AdamW update runs in registers, and the four results go out
-// twice -- in place, and at their stream offsets in the chunk buffer.  The same registers feed
-// four CRC folding states (three 16-byte-per-lane streams, one 8-byte-per-lane stream), so the
-// snapshot is never read back.  Rows are aligned to the END of the tile: a tile whose length is
-// not a multiple of 256 has a partial FIRST row, whose missing leading elements are zeros that
-// do not change a CRC register started from 0.  At the end of the tile each stream's state is
-// reduced to a register, multiplied by x^(8 * distance to the end of its chunk) and XORed into
-// crcs[chunk] with an atomic; XOR is commutative, so the result does not depend on the order in
-// which tiles finish.  A prepare kernel zeroes crcs[] and the zero tail of the last chunk; a
-// finish kernel adds the preset/complement term.
+// twice -- in place, and at their stream offsets in the chunk buffer -- plus once into LDS,
+// from where four folding wavefronts (one per output stream) take them into their CRC states,
+// so the snapshot is never read back from memory.  Rows are aligned to the END of the tile: a
+// tile whose length is not a multiple of 256 has a partial FIRST row, whose missing leading
+// elements are zeros that do not change a CRC register started from 0.  At the end of the tile
+// each stream's state is reduced to a register, multiplied by x^(8 * distance to the end of its
+// chunk) and XORed into crcs[chunk] with an atomic; XOR is commutative, so the result does not
+// depend on the order in which tiles finish.  A prepare kernel zeroes crcs[] and the zero tail
+// of the last chunk; a finish kernel adds the preset/complement term.
 #include "fused.hpp"
 
 #include "fold.h"
@@ -21,13 +21,16 @@ namespace ffsnap {
 
 namespace {
 
-constexpr int kWavesPerBlock = 4;
-using F32Fold = Fold16x10;  // 16 bytes per lane per row
+constexpr int kUpdateWaves = 4;  // one row of a batch each
+constexpr int kFoldWaves = 4;    // one output stream each
+constexpr int kWavesPerBlock = kUpdateWaves + kFoldWaves;
+constexpr int kBatchRows = kUpdateWaves;
+using F32Fold = Fold16x16;  // 16 bytes per lane per row (parameter tiles)
 using B16Fold = Fold8x20;   // 8 bytes per lane per row
+using RawFold = Fold16x10;  // RAW copy tiles
 constexpr int kPhases = 5;  // rows folded between two physical rotations of the state
-static_assert(kPhases <= F32Fold::NE && kPhases <= B16Fold::NE, "rotation step");
+static_assert(kPhases <= RawFold::NE, "rotation step");
 constexpr int kRowElems = 256;
-constexpr int kBatch = 1;  // rows loaded, updated and stored together
 
 __device__ __forceinline__ float bits_to_f32(uint32_t u) { return __uint_as_float(u); }
 __device__ __forceinline__ uint32_t f32_to_bits(float f) { return __float_as_uint(f); }
@@ -73,17 +76,49 @@ __device__ __forceinline__ void add_piece(uint32_t* __restrict__ crcs, const Wor
 }
 
 // ---- parameter tile ----------------------------------------------------------------------------
+//
+// A workgroup of 8 wavefronts owns one parameter tile.  Wavefronts 0..3 update: in every batch of
+// 4 rows each takes one row, runs the AdamW update in registers, stores the results twice (in
+// place, snapshot) and leaves a copy in LDS.  Wavefronts 4..7 fold: each owns ONE output stream
+// (w16, master, m, v) and one CRC state, and folds the 4 rows of the previous batch out of LDS.
+// One barrier per batch separates writers and readers of the two LDS batch buffers.  Splitting
+// the roles keeps every wavefront's register set small (one fold state instead of four), which
+// lets several wavefronts share a SIMD and overlap arithmetic with memory waits.
 
-__device__ __forceinline__ void run_param_tile(const WorkTile& t, const uint8_t* __restrict__ grad,
-                                               uint8_t* __restrict__ chunks,
-                                               uint32_t* __restrict__ crcs, const FusedConsts& C,
-                                               const Lds& lds, int lane)
+struct Batch {          // results of 4 rows, as they lie in the streams
+    uint32_t w[kBatchRows][128];
+    uint32_t p[kBatchRows][256];
+    uint32_t m[kBatchRows][256];
+    uint32_t v[kBatchRows][256];
+};
+
+struct RowIn {
+    u32x2 g;
+    u32x4 p, m, v;
+};
+
+struct TileGeom {
+    int n, pad_el, rows, n_batches, pad_rows;
+};
+
+__device__ __forceinline__ TileGeom tile_geom(const WorkTile& t)
 {
-    const int n = static_cast<int>(t.n);
-    const int pad_el = (kRowElems - n % kRowElems) % kRowElems;  // missing in front of row 0
-    const int rows = (n + pad_el) / kRowElems;
-    const int pad_rows = (kPhases - rows % kPhases) % kPhases;
+    TileGeom g;
+    g.n = static_cast<int>(t.n);
+    g.pad_el = (kRowElems - g.n % kRowElems) % kRowElems;  // elements missing in front of row 0
+    g.rows = (g.n + g.pad_el) / kRowElems;
+    g.n_batches = (g.rows + kBatchRows - 1) / kBatchRows;
+    g.pad_rows = g.n_batches * kBatchRows - g.rows;  // virtual zero rows in front of row 0
+    return g;
+}
 
+// Update wavefront `u` (0..3): rows u - pad_rows, u - pad_rows + 4, ...
+__device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G,
+                                            const uint8_t* __restrict__ grad,
+                                            uint8_t* __restrict__ chunks,
+                                            uint32_t* __restrict__ crcs, const FusedConsts& C,
+                                            Batch (&buf)[2], int u, int lane)
+{
     uint8_t* const tw = reinterpret_cast<uint8_t*>(t.ptr[0]);
     uint8_t* const tp = reinterpret_cast<uint8_t*>(t.ptr[1]);
     uint8_t* const tm = reinterpret_cast<uint8_t*>(t.ptr[2]);
@@ -93,198 +128,170 @@ __device__ __forceinline__ void run_param_tile(const WorkTile& t, const uint8_t*
     uint8_t* const sp = chunks + t.soff[1];
     uint8_t* const sm = chunks + t.soff[2];
     uint8_t* const sv = chunks + t.soff[3];
+    const int head_lane = G.pad_el / 4, head_sub = G.pad_el % 4;  // where element 0 sits in row 0
 
-    uint32_t Sp[F32Fold::NE][4], Sm[F32Fold::NE][4], Sv[F32Fold::NE][4], Sw[B16Fold::NE][2];
-    static_for<F32Fold::NE>([&](auto e) {
-        static_for<4>([&](auto f) { Sp[e][f] = 0; Sm[e][f] = 0; Sv[e][f] = 0; });
-    });
-    static_for<B16Fold::NE>([&](auto e) { Sw[e][0] = 0; Sw[e][1] = 0; });
-
-    // lane and sub-position of element 0 (for the head pieces of split elements)
-    const int head_lane = pad_el / 4, head_sub = pad_el % 4;
-
-    struct RowIn {
-        u32x2 g;
-        u32x4 p, m, v;
+    // A row can use vector accesses if every lane holds 4 real elements.
+    auto full_row = [&](int r) { return r > 0 || (r == 0 && G.pad_el == 0); };
+    // Vector loads of row r, redirected to the last row when r is not a full row of the tile
+    // (always in bounds; the data is then not used).
+    auto load_row = [&](int r) -> RowIn {
+        const int rr = (full_row(r) && r < G.rows) ? r : G.rows - 1;
+        const int j0 = rr * kRowElems + 4 * lane - G.pad_el;
+        RowIn in;
+        in.g = load8_unaligned<true>(tg + 2 * j0);
+        in.p = load16_unaligned<true>(tp + 4 * j0);
+        in.m = load16_unaligned<true>(tm + 4 * j0);
+        in.v = load16_unaligned<true>(tv + 4 * j0);
+        return in;
     };
-    // Only the folding step depends on how far the state registers have rotated, so it alone is
-    // selected by a switch on the phase.  Unrolling a whole rotation (20 rows) would put ~90 KB
-    // of code in the loop; instead the rotation is undone with register moves every kPhases
-    // rows, which keeps the loop body small enough for the instruction cache.  Starting at phase
-    // pad_rows makes the last row end a block, so the state ends in logical order.
-    auto fold_all = [&](int r, uint32_t (&fw)[2], uint32_t (&fp)[4], uint32_t (&fm)[4],
-                        uint32_t (&fv)[4]) {
-        const int phase = (r + pad_rows) % kPhases;
-        static_for<kPhases>([&](auto Jc) {
-            constexpr int J = Jc;
-            if (phase == J) {
-                fold_row<B16Fold, J>(Sw, fw);
-                fold_row<F32Fold, J>(Sp, fp);
-                fold_row<F32Fold, J>(Sm, fm);
-                fold_row<F32Fold, J>(Sv, fv);
-                if constexpr (J == kPhases - 1) {
-                    rotate_state<B16Fold, kPhases>(Sw);
-                    rotate_state<F32Fold, kPhases>(Sp);
-                    rotate_state<F32Fold, kPhases>(Sm);
-                    rotate_state<F32Fold, kPhases>(Sv);
-                }
-            }
-        });
-    };
-    // Update one row in registers and fold it; the row's results replace its inputs (g becomes
-    // the packed bf16 weights).
-    auto update_row = [&](int r, RowIn& io) {
-        uint32_t gb[4] = {io.g.x & 0xFFFFu, io.g.x >> 16, io.g.y & 0xFFFFu, io.g.y >> 16};
-        uint32_t wb[4];
-        float p[4] = {bits_to_f32(io.p.x), bits_to_f32(io.p.y), bits_to_f32(io.p.z), bits_to_f32(io.p.w)};
-        float m[4] = {bits_to_f32(io.m.x), bits_to_f32(io.m.y), bits_to_f32(io.m.z), bits_to_f32(io.m.w)};
-        float v[4] = {bits_to_f32(io.v.x), bits_to_f32(io.v.y), bits_to_f32(io.v.z), bits_to_f32(io.v.w)};
-#pragma unroll
-        for (int s = 0; s < 4; s++) adam_element(C.adam, gb[s], p[s], m[s], v[s], wb[s]);
-        uint32_t fw[2] = {wb[0] | (wb[1] << 16), wb[2] | (wb[3] << 16)};
-        uint32_t fp[4] = {f32_to_bits(p[0]), f32_to_bits(p[1]), f32_to_bits(p[2]), f32_to_bits(p[3])};
-        uint32_t fm[4] = {f32_to_bits(m[0]), f32_to_bits(m[1]), f32_to_bits(m[2]), f32_to_bits(m[3])};
-        uint32_t fv[4] = {f32_to_bits(v[0]), f32_to_bits(v[1]), f32_to_bits(v[2]), f32_to_bits(v[3])};
-        io.g = u32x2{fw[0], fw[1]};
-        io.p = u32x4{fp[0], fp[1], fp[2], fp[3]};
-        io.m = u32x4{fm[0], fm[1], fm[2], fm[3]};
-        io.v = u32x4{fv[0], fv[1], fv[2], fv[3]};
-        // split first element (row 0 of a tile that starts on a full row): its first two bytes
-        // close the previous chunk
-        if (r == 0 && t.head_split && lane == head_lane) {
-            uint32_t* const fx[3] = {fp, fm, fv};
-#pragma unroll
-            for (int x = 1; x <= 3; x++) {
-                if (t.head_split & (1u << x)) {
-                    const uint32_t d = fx[x - 1][0];  // pad_el == 0 here: element 0 is sub 0
-                    // two message bytes in the low half are M(x) * x^16; their register is
-                    // M(x) * x^32
-                    add_piece(crcs, t, 3 + x, gf2_mul(d & 0xFFFFu, C.x16));
-                    fx[x - 1][0] = d & 0xFFFF0000u;
-                }
-            }
-        }
-        fold_all(r, fw, fp, fm, fv);
-    };
+    const bool can_prefetch = G.rows > 1 || G.pad_el == 0;  // the last row is a full row
 
-    int r_first = 0;
-    if (pad_el != 0) {
-        // partial first row: element by element; absent elements stay zero and fold as zeros
-        r_first = 1;
-        const int j0 = 4 * lane - pad_el;
-        uint32_t gb[4], wb[4];
-        float p[4], m[4], v[4];
+    RowIn q0, q1;  // inputs of this wavefront's next two rows
+    q0 = q1 = RowIn{u32x2{0, 0}, u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}};
+    if (can_prefetch) {
+        q0 = load_row(u - G.pad_rows);
+        q1 = load_row(u - G.pad_rows + kBatchRows);
+    }
+
+    for (int b = 0; b <= G.n_batches; b++) {
+        if (b < G.n_batches) {
+            const int r = b * kBatchRows + u - G.pad_rows;
+            Batch& out = buf[b & 1];
+            uint32_t fw[2] = {0, 0}, fp[4] = {0, 0, 0, 0}, fm[4] = {0, 0, 0, 0}, fv[4] = {0, 0, 0, 0};
+            const RowIn cur = q0;
+            q0 = q1;
+            if (can_prefetch) q1 = load_row(r + 2 * kBatchRows);
+            if (r >= 0) {
+                const int j0 = r * kRowElems + 4 * lane - G.pad_el;  // first element of the lane
+                uint32_t gb[4], wb[4];
+                float p[4], m[4], v[4];
+                if (full_row(r)) {
+                    gb[0] = cur.g.x & 0xFFFFu; gb[1] = cur.g.x >> 16;
+                    gb[2] = cur.g.y & 0xFFFFu; gb[3] = cur.g.y >> 16;
+                    p[0] = bits_to_f32(cur.p.x); p[1] = bits_to_f32(cur.p.y);
+                    p[2] = bits_to_f32(cur.p.z); p[3] = bits_to_f32(cur.p.w);
+                    m[0] = bits_to_f32(cur.m.x); m[1] = bits_to_f32(cur.m.y);
+                    m[2] = bits_to_f32(cur.m.z); m[3] = bits_to_f32(cur.m.w);
+                    v[0] = bits_to_f32(cur.v.x); v[1] = bits_to_f32(cur.v.y);
+                    v[2] = bits_to_f32(cur.v.z); v[3] = bits_to_f32(cur.v.w);
 #pragma unroll
-        for (int s = 0; s < 4; s++) {
-            const int j = j0 + s;
-            gb[s] = 0; wb[s] = 0; p[s] = 0.f; m[s] = 0.f; v[s] = 0.f;
-            if (j >= 0) {
-                gb[s] = *as_global(reinterpret_cast<const uint16_t*>(tg + 2 * j));
-                p[s] = *as_global(reinterpret_cast<const float*>(tp + 4 * j));
-                m[s] = *as_global(reinterpret_cast<const float*>(tm + 4 * j));
-                v[s] = *as_global(reinterpret_cast<const float*>(tv + 4 * j));
-                adam_element(C.adam, gb[s], p[s], m[s], v[s], wb[s]);
-                *as_global(reinterpret_cast<uint16_t*>(tw + 2 * j)) = static_cast<uint16_t>(wb[s]);
-                *as_global(reinterpret_cast<float*>(tp + 4 * j)) = p[s];
-                *as_global(reinterpret_cast<float*>(tm + 4 * j)) = m[s];
-                *as_global(reinterpret_cast<float*>(tv + 4 * j)) = v[s];
-                *as_global(reinterpret_cast<uint16_t*>(sw + 2 * j)) = static_cast<uint16_t>(wb[s]);
-                // stream offsets of fp32 segments may be 2 mod 4: halfword stores
-                const uint32_t pb = f32_to_bits(p[s]), mb = f32_to_bits(m[s]), vb = f32_to_bits(v[s]);
-                uint16_t* qp = reinterpret_cast<uint16_t*>(sp + 4 * j);
-                uint16_t* qm = reinterpret_cast<uint16_t*>(sm + 4 * j);
-                uint16_t* qv = reinterpret_cast<uint16_t*>(sv + 4 * j);
-                qp[0] = static_cast<uint16_t>(pb); qp[1] = static_cast<uint16_t>(pb >> 16);
-                qm[0] = static_cast<uint16_t>(mb); qm[1] = static_cast<uint16_t>(mb >> 16);
-                qv[0] = static_cast<uint16_t>(vb); qv[1] = static_cast<uint16_t>(vb >> 16);
-            }
-        }
-        uint32_t fw[2] = {wb[0] | (wb[1] << 16), wb[2] | (wb[3] << 16)};
-        uint32_t fp[4] = {f32_to_bits(p[0]), f32_to_bits(p[1]), f32_to_bits(p[2]), f32_to_bits(p[3])};
-        uint32_t fm[4] = {f32_to_bits(m[0]), f32_to_bits(m[1]), f32_to_bits(m[2]), f32_to_bits(m[3])};
-        uint32_t fv[4] = {f32_to_bits(v[0]), f32_to_bits(v[1]), f32_to_bits(v[2]), f32_to_bits(v[3])};
-        if (t.head_split && lane == head_lane) {
-            uint32_t* const fx[3] = {fp, fm, fv};
-#pragma unroll
-            for (int x = 1; x <= 3; x++) {
-                if (t.head_split & (1u << x)) {
+                    for (int s = 0; s < 4; s++) adam_element(C.adam, gb[s], p[s], m[s], v[s], wb[s]);
+                    const u32x2 w2 = {wb[0] | (wb[1] << 16), wb[2] | (wb[3] << 16)};
+                    const u32x4 po = {f32_to_bits(p[0]), f32_to_bits(p[1]), f32_to_bits(p[2]), f32_to_bits(p[3])};
+                    const u32x4 mo = {f32_to_bits(m[0]), f32_to_bits(m[1]), f32_to_bits(m[2]), f32_to_bits(m[3])};
+                    const u32x4 vo = {f32_to_bits(v[0]), f32_to_bits(v[1]), f32_to_bits(v[2]), f32_to_bits(v[3])};
+                    store8_unaligned<true>(tw + 2 * j0, w2);
+                    store16_unaligned<true>(tp + 4 * j0, po);
+                    store16_unaligned<true>(tm + 4 * j0, mo);
+                    store16_unaligned<true>(tv + 4 * j0, vo);
+                    store8_unaligned<true>(sw + 2 * j0, w2);
+                    store16_unaligned<true>(sp + 4 * j0, po);
+                    store16_unaligned<true>(sm + 4 * j0, mo);
+                    store16_unaligned<true>(sv + 4 * j0, vo);
+                } else {
+                    // partial first row: element by element; absent elements stay zero
 #pragma unroll
                     for (int s = 0; s < 4; s++) {
-                        if (s == head_sub) {
-                            const uint32_t d = fx[x - 1][s];
-                            add_piece(crcs, t, 3 + x, gf2_mul(d & 0xFFFFu, C.x16));
-                            fx[x - 1][s] = d & 0xFFFF0000u;
+                        const int j = j0 + s;
+                        gb[s] = 0; wb[s] = 0; p[s] = 0.f; m[s] = 0.f; v[s] = 0.f;
+                        if (j >= 0) {
+                            gb[s] = *as_global(reinterpret_cast<const uint16_t*>(tg + 2 * j));
+                            p[s] = *as_global(reinterpret_cast<const float*>(tp + 4 * j));
+                            m[s] = *as_global(reinterpret_cast<const float*>(tm + 4 * j));
+                            v[s] = *as_global(reinterpret_cast<const float*>(tv + 4 * j));
+                            adam_element(C.adam, gb[s], p[s], m[s], v[s], wb[s]);
+                            *as_global(reinterpret_cast<uint16_t*>(tw + 2 * j)) = static_cast<uint16_t>(wb[s]);
+                            *as_global(reinterpret_cast<float*>(tp + 4 * j)) = p[s];
+                            *as_global(reinterpret_cast<float*>(tm + 4 * j)) = m[s];
+                            *as_global(reinterpret_cast<float*>(tv + 4 * j)) = v[s];
+                            *as_global(reinterpret_cast<uint16_t*>(sw + 2 * j)) = static_cast<uint16_t>(wb[s]);
+                            // stream offsets of fp32 segments may be 2 mod 4: halfword stores
+                            const uint32_t pb = f32_to_bits(p[s]), mb = f32_to_bits(m[s]),
+                                           vb = f32_to_bits(v[s]);
+                            uint16_t* qp = reinterpret_cast<uint16_t*>(sp + 4 * j);
+                            uint16_t* qm = reinterpret_cast<uint16_t*>(sm + 4 * j);
+                            uint16_t* qv = reinterpret_cast<uint16_t*>(sv + 4 * j);
+                            *as_global(qp) = static_cast<uint16_t>(pb);
+                            *as_global(qp + 1) = static_cast<uint16_t>(pb >> 16);
+                            *as_global(qm) = static_cast<uint16_t>(mb);
+                            *as_global(qm + 1) = static_cast<uint16_t>(mb >> 16);
+                            *as_global(qv) = static_cast<uint16_t>(vb);
+                            *as_global(qv + 1) = static_cast<uint16_t>(vb >> 16);
+                        }
+                    }
+                }
+                fw[0] = wb[0] | (wb[1] << 16);
+                fw[1] = wb[2] | (wb[3] << 16);
+#pragma unroll
+                for (int s = 0; s < 4; s++) {
+                    fp[s] = f32_to_bits(p[s]);
+                    fm[s] = f32_to_bits(m[s]);
+                    fv[s] = f32_to_bits(v[s]);
+                }
+                // split first element: its first two bytes close the previous chunk and must not
+                // enter this tile's CRC of that stream
+                if (r == 0 && t.head_split && lane == head_lane) {
+                    uint32_t* const fx[3] = {fp, fm, fv};
+#pragma unroll
+                    for (int x = 1; x <= 3; x++) {
+                        if (t.head_split & (1u << x)) {
+#pragma unroll
+                            for (int s = 0; s < 4; s++) {
+                                if (s == head_sub) {
+                                    const uint32_t d = fx[x - 1][s];
+                                    // two message bytes in the low half are M(x) * x^16; their
+                                    // register is M(x) * x^32
+                                    add_piece(crcs, t, 3 + x, gf2_mul(d & 0xFFFFu, C.x16));
+                                    fx[x - 1][s] = d & 0xFFFF0000u;
+                                }
+                            }
                         }
                     }
                 }
             }
+            // copy for the folding wavefronts (zeros for a virtual row)
+            *reinterpret_cast<u32x2*>(&out.w[u][2 * lane]) = u32x2{fw[0], fw[1]};
+            *reinterpret_cast<u32x4*>(&out.p[u][4 * lane]) = u32x4{fp[0], fp[1], fp[2], fp[3]};
+            *reinterpret_cast<u32x4*>(&out.m[u][4 * lane]) = u32x4{fm[0], fm[1], fm[2], fm[3]};
+            *reinterpret_cast<u32x4*>(&out.v[u][4 * lane]) = u32x4{fv[0], fv[1], fv[2], fv[3]};
         }
-        fold_all(0, fw, fp, fm, fv);
+        __syncthreads();
     }
+}
 
-    // Full rows in batches of kBatch.  Per batch and per stream the kBatch loads, and later the
-    // kBatch stores, are issued back to back, so each stream presents 4 KiB of consecutive
-    // addresses to the memory system at a time (measured: +10 % bandwidth over row-by-row
-    // issue).  The inputs of the next batch are requested before the current one is updated.
-    // Loads past the last row are redirected to the last row (always in bounds, never used).
-    if (r_first < rows) {
-        auto load_batch = [&](RowIn (&q)[kBatch], int r0) {
-            static_for<kBatch>([&](auto k) {
-                const int rr = r0 + k;
-                const int j0 = (rr < rows ? rr : rows - 1) * kRowElems + 4 * lane - pad_el;
-                q[k].g = load8_unaligned<true>(tg + 2 * j0);
+// Folding wavefront of stream x (0 = w16, 1..3 = master, m, v).
+template <class F, int DW>
+__device__ __forceinline__ uint32_t fold_stream(const TileGeom& G, Batch (&buf)[2], int x, int lane,
+                                                const uint32_t* tab, uint32_t x32,
+                                                const uint32_t (&zl)[6])
+{
+    constexpr int NE = F::NE;
+    static_assert(NE % kBatchRows == 0 && F::NF == DW, "a batch never straddles the rotation");
+    uint32_t S[NE][DW];
+    static_for<NE>([&](auto e) { static_for<DW>([&](auto f) { S[e][f] = 0; }); });
+    // start the rotation so that it is back at zero after the last batch
+    int phase = (NE - (G.n_batches * kBatchRows) % NE) % NE;
+    for (int b = 0; b <= G.n_batches; b++) {
+        if (b >= 1) {
+            const Batch& in = buf[(b - 1) & 1];
+            uint32_t d[kBatchRows][DW];
+            static_for<kBatchRows>([&](auto k) {
+                const uint32_t* row = (DW == 2) ? &in.w[k][2 * lane]
+                                                : (x == 1 ? &in.p[k][4 * lane]
+                                                          : (x == 2 ? &in.m[k][4 * lane] : &in.v[k][4 * lane]));
+                static_for<DW>([&](auto f) { d[k][f] = row[f]; });
             });
-            static_for<kBatch>([&](auto k) {
-                const int rr = r0 + k;
-                const int j0 = (rr < rows ? rr : rows - 1) * kRowElems + 4 * lane - pad_el;
-                q[k].p = load16_unaligned<true>(tp + 4 * j0);
+            static_for<NE / kBatchRows>([&](auto Qc) {
+                constexpr int Q = Qc;
+                if (phase == Q * kBatchRows) {
+                    static_for<kBatchRows>([&](auto k) { fold_row<F, Q * kBatchRows + k>(S, d[k]); });
+                }
             });
-            static_for<kBatch>([&](auto k) {
-                const int rr = r0 + k;
-                const int j0 = (rr < rows ? rr : rows - 1) * kRowElems + 4 * lane - pad_el;
-                q[k].m = load16_unaligned<true>(tm + 4 * j0);
-            });
-            static_for<kBatch>([&](auto k) {
-                const int rr = r0 + k;
-                const int j0 = (rr < rows ? rr : rows - 1) * kRowElems + 4 * lane - pad_el;
-                q[k].v = load16_unaligned<true>(tv + 4 * j0);
-            });
-        };
-        RowIn cur[kBatch], nxt[kBatch];
-        load_batch(nxt, r_first);
-        for (int r0 = r_first; r0 < rows; r0 += kBatch) {
-            static_for<kBatch>([&](auto k) { cur[k] = nxt[k]; });
-            load_batch(nxt, r0 + kBatch);
-            // one copy of the update code: rows rotate through cur[0], results queue up behind
-            for (int k = 0; k < kBatch; k++) {
-                RowIn x = cur[0];
-                static_for<kBatch - 1>([&](auto i) { cur[i] = cur[i + 1]; });
-                if (r0 + k < rows) update_row(r0 + k, x);
-                cur[kBatch - 1] = x;
-            }
-            const int nb = rows - r0;  // real rows in this batch (>= kBatch except at the end)
-            auto j0_of = [&](int k) { return (r0 + k) * kRowElems + 4 * lane - pad_el; };
-            static_for<kBatch>([&](auto k) { if (k < nb) store8_unaligned(tw + 2 * j0_of(k), cur[k].g); });
-            static_for<kBatch>([&](auto k) { if (k < nb) store16_unaligned(tp + 4 * j0_of(k), cur[k].p); });
-            static_for<kBatch>([&](auto k) { if (k < nb) store16_unaligned(tm + 4 * j0_of(k), cur[k].m); });
-            static_for<kBatch>([&](auto k) { if (k < nb) store16_unaligned(tv + 4 * j0_of(k), cur[k].v); });
-            static_for<kBatch>([&](auto k) { if (k < nb) store8_unaligned<true>(sw + 2 * j0_of(k), cur[k].g); });
-            static_for<kBatch>([&](auto k) { if (k < nb) store16_unaligned<true>(sp + 4 * j0_of(k), cur[k].p); });
-            static_for<kBatch>([&](auto k) { if (k < nb) store16_unaligned<true>(sm + 4 * j0_of(k), cur[k].m); });
-            static_for<kBatch>([&](auto k) { if (k < nb) store16_unaligned<true>(sv + 4 * j0_of(k), cur[k].v); });
+            phase = (phase + kBatchRows) % NE;
         }
+        __syncthreads();
     }
-
-    const uint32_t rw = reduce_state<B16Fold>(Sw, lds.tab8, C.x32, C.z8);
-    const uint32_t rp = reduce_state<F32Fold>(Sp, lds.tab16, C.x32, C.z16);
-    const uint32_t rm = reduce_state<F32Fold>(Sm, lds.tab16, C.x32, C.z16);
-    const uint32_t rv = reduce_state<F32Fold>(Sv, lds.tab16, C.x32, C.z16);
-    if (lane == 0) {
-        add_piece(crcs, t, 0, rw);
-        add_piece(crcs, t, 1, rp);
-        add_piece(crcs, t, 2, rm);
-        add_piece(crcs, t, 3, rv);
-    }
+    return reduce_state<F>(S, tab, x32, zl);
 }
 
 // ---- RAW tile: plain copy into the snapshot -----------------------------------------------------
@@ -293,7 +300,7 @@ __device__ __forceinline__ void run_raw_tile(const WorkTile& t, uint8_t* __restr
                                              uint32_t* __restrict__ crcs, const FusedConsts& C,
                                              const Lds& lds, int lane)
 {
-    constexpr int NE = F32Fold::NE;
+    constexpr int NE = RawFold::NE;
     const int n = static_cast<int>(t.n);  // bytes, even
     const int pad_b = (1024 - n % 1024) % 1024;
     const int rows = (n + pad_b) / 1024;
@@ -325,12 +332,12 @@ __device__ __forceinline__ void run_raw_tile(const WorkTile& t, uint8_t* __restr
         static_for<kPhases>([&](auto Jc) {
             constexpr int J = Jc;
             if (phase == J) {
-                fold_row<F32Fold, J>(S, d);
-                if constexpr (J == kPhases - 1) rotate_state<F32Fold, kPhases>(S);
+                fold_row<RawFold, J>(S, d);
+                if constexpr (J == kPhases - 1) rotate_state<RawFold, kPhases>(S);
             }
         });
     }
-    const uint32_t reg = reduce_state<F32Fold>(S, lds.tab16, C.x32, C.z16);
+    const uint32_t reg = reduce_state<RawFold>(S, lds.tab16, C.x32, C.z16);
     if (lane == 0) add_piece(crcs, t, 0, reg);
 }
 
@@ -340,16 +347,17 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
     FusedConsts C)
 {
     __shared__ Lds lds;
+    __shared__ Batch buf[2];
     for (int i = threadIdx.x; i < 1024; i += blockDim.x) {
         lds.tab16[i] = tabs[i];
         lds.tab8[i] = tabs[1024 + i];
     }
     __syncthreads();
     const int lane = threadIdx.x & (kWaveSize - 1);
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
-    const uint32_t ti = blockIdx.x * kWavesPerBlock + wave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
+    const uint32_t ti = blockIdx.x;  // one tile per workgroup
     if (ti >= n_tiles) return;
-    // the tile descriptor is wave-uniform: read it through scalar registers
+    // the tile descriptor is uniform: read it through scalar registers
     WorkTile t;
     {
         const uint32_t* src = reinterpret_cast<const uint32_t*>(tiles + ti);
@@ -358,11 +366,24 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
         for (unsigned i = 0; i < sizeof(WorkTile) / 4; i++)
             dst[i] = __builtin_amdgcn_readfirstlane(src[i]);
     }
-    if (t.kind == kWorkParam) {
+    if (t.kind != kWorkParam) {
+        // RAW bytes: one wavefront copies and folds; no barrier follows, the others just leave
+        if (wave == 0) run_raw_tile(t, chunks, crcs, C, lds, lane);
+        return;
+    }
+    // every wavefront of the workgroup passes the same n_batches + 1 barriers
+    const TileGeom G = tile_geom(t);
+    if (wave < kUpdateWaves) {
         const uint8_t* grad = reinterpret_cast<const uint8_t*>(grads[t.grad_index]);
-        run_param_tile(t, grad, chunks, crcs, C, lds, lane);
+        update_role(t, G, grad, chunks, crcs, C, buf, wave, lane);
     } else {
-        run_raw_tile(t, chunks, crcs, C, lds, lane);
+        const int x = wave - kUpdateWaves;
+        uint32_t reg;
+        if (x == 0)
+            reg = fold_stream<B16Fold, 2>(G, buf, x, lane, lds.tab8, C.x32, C.z8);
+        else
+            reg = fold_stream<F32Fold, 4>(G, buf, x, lane, lds.tab16, C.x32, C.z16);
+        if (lane == 0) add_piece(crcs, t, x, reg);
     }
 }
 
@@ -420,7 +441,7 @@ hipError_t launch_fused(const WorkTile* tiles, uint32_t n_tiles, const uint64_t*
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (n_tiles) {
-        const unsigned grid = (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+        const unsigned grid = n_tiles;
         hipLaunchKernelGGL(fused_kernel, dim3(grid), dim3(kWaveSize * kWavesPerBlock), 0, stream,
                            tiles, n_tiles, grads, tabs, c, crcs, consts);
         e = hipGetLastError();
