@@ -132,26 +132,21 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
 
     // A row can use vector accesses if every lane holds 4 real elements.
     auto full_row = [&](int r) { return r > 0 || (r == 0 && G.pad_el == 0); };
-    // Vector loads of row r, redirected to the last row when r is not a full row of the tile
-    // (always in bounds; the data is then not used).
-    auto load_row = [&](int r) -> RowIn {
-        const int rr = (full_row(r) && r < G.rows) ? r : G.rows - 1;
-        const int j0 = rr * kRowElems + 4 * lane - G.pad_el;
-        RowIn in;
-        in.g = load8_unaligned<true>(tg + 2 * j0);
-        in.p = load16_unaligned<true>(tp + 4 * j0);
-        in.m = load16_unaligned<true>(tm + 4 * j0);
-        in.v = load16_unaligned<true>(tv + 4 * j0);
-        return in;
+    // Vector loads of row r if it is a full row of the tile (nothing is requested otherwise).
+    auto load_row = [&](int r, RowIn& in) {
+        if (full_row(r) && r < G.rows) {
+            const int j0 = r * kRowElems + 4 * lane - G.pad_el;
+            in.g = load8_unaligned<true>(tg + 2 * j0);
+            in.p = load16_unaligned<true>(tp + 4 * j0);
+            in.m = load16_unaligned<true>(tm + 4 * j0);
+            in.v = load16_unaligned<true>(tv + 4 * j0);
+        }
     };
-    const bool can_prefetch = G.rows > 1 || G.pad_el == 0;  // the last row is a full row
 
     RowIn q0, q1;  // inputs of this wavefront's next two rows
     q0 = q1 = RowIn{u32x2{0, 0}, u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}};
-    if (can_prefetch) {
-        q0 = load_row(u - G.pad_rows);
-        q1 = load_row(u - G.pad_rows + kBatchRows);
-    }
+    load_row(u - G.pad_rows, q0);
+    load_row(u - G.pad_rows + kBatchRows, q1);
 
     for (int b = 0; b <= G.n_batches; b++) {
         if (b < G.n_batches) {
@@ -160,7 +155,7 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
             uint32_t fw[2] = {0, 0}, fp[4] = {0, 0, 0, 0}, fm[4] = {0, 0, 0, 0}, fv[4] = {0, 0, 0, 0};
             const RowIn cur = q0;
             q0 = q1;
-            if (can_prefetch) q1 = load_row(r + 2 * kBatchRows);
+            load_row(r + 2 * kBatchRows, q1);
             if (r >= 0) {
                 const int j0 = r * kRowElems + 4 * lane - G.pad_el;  // first element of the lane
                 uint32_t gb[4], wb[4];
