@@ -80,6 +80,9 @@ typedef struct {
 
 /* ff_restore flags */
 #define FF_RESTORE_VERIFY_ONLY 1u /* recompute and compare CRCs, write bad[]/n_bad, scatter nothing */
+#define FF_RESTORE_SKIP_BAD 2u    /* verify first, then scatter only the chunks whose CRC matched:
+                                     tensor ranges covered by a bad chunk keep their old contents
+                                     (the buffer is read twice: 3 B of traffic per payload byte)  */
 
 #define FF_MIN_CHUNK_BYTES 1024ull
 #define FF_MAX_CHUNK_BYTES (1ull << 30)
@@ -126,10 +129,30 @@ int ff_pack(const ff_plan *plan, void *chunks, uint32_t *crcs, void *hip_stream)
  * segment's bytes out of the buffer into the plan's tensors -- from good and bad chunks alike:
  * the caller must treat tensor ranges that a bad chunk covers as invalid.  chunks: DEVICE,
  * 16-byte aligned, buffer_bytes.  crcs: DEVICE, num_chunks.  bad: DEVICE, num_chunks uint32,
- * each set to 0 or 1.  n_bad: DEVICE, one uint64.  flags: 0 or FF_RESTORE_VERIFY_ONLY.
+ * each set to 0 or 1.  n_bad: DEVICE, one uint64.  flags: 0, FF_RESTORE_VERIFY_ONLY or
+ * FF_RESTORE_SKIP_BAD.
  */
 int ff_restore(const ff_plan *plan, const void *chunks, const uint32_t *crcs, uint32_t *bad,
                uint64_t *n_bad, uint32_t flags, void *hip_stream);
+
+/*
+ * Selective state loading: the same as ff_restore for the n_ids chunks named in chunk_ids only
+ * (HOST array, strictly ascending, each < num_chunks) -- the chunks a worker re-fetched after a
+ * first restore flagged them, or the part of the state another source supplies (section 4.2:
+ * state that instant checkpointing cannot supply comes from a fallback).  bad[j] is written for
+ * the listed chunks alone, *n_bad counts the bad ones among them, tensor bytes outside the
+ * listed chunks are not touched.  Flags as for ff_restore.  FF_ERR_INVALID for an id out of
+ * range or a list that is not strictly ascending.  n_ids == 0 only sets *n_bad = 0.
+ */
+int ff_restore_chunks(const ff_plan *plan, const void *chunks, const uint32_t *crcs,
+                      const uint64_t *chunk_ids, uint64_t n_ids, uint32_t *bad, uint64_t *n_bad,
+                      uint32_t flags, void *hip_stream);
+
+/* Which tensor ranges a chunk covers: [*begin, *end) is the chunk's payload range in stream
+ * coordinates (clipped to N), and the non-empty segments *first_seg .. *first_seg + *n_seg - 1
+ * intersect it (use ff_plan_segment_range for their stream ranges).  Host-only query. */
+int ff_plan_chunk_span(const ff_plan *plan, uint64_t chunk, uint64_t *first_seg, uint64_t *n_seg,
+                       uint64_t *begin, uint64_t *end);
 
 typedef struct {
     float lr, beta1, beta2, eps, weight_decay;

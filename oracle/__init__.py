@@ -61,6 +61,9 @@ def lib():
         L.orc_verify_chunks.argtypes = [ctypes.c_void_p, u32p, u64, u32p, u64, u64]
         L.orc_scatter_segments.restype = None
         L.orc_scatter_segments.argtypes = [vpp, u64p, u64, ctypes.c_void_p, u64, u64]
+        L.orc_restore_chunks.restype = u64
+        L.orc_restore_chunks.argtypes = [vpp, u64p, u64, u64, ctypes.c_void_p, u32p, u64p, u64,
+                                         u32p, ctypes.c_int]
         L.orc_f32_to_bf16.restype = ctypes.c_uint16
         L.orc_f32_to_bf16.argtypes = [ctypes.c_float]
         L.orc_adam_f32.restype = None
@@ -193,6 +196,22 @@ def restore(segments, chunk_bytes, buffer, crcs, threads=1):
         with ThreadPoolExecutor(threads) as ex:
             list(ex.map(work, rs))
     return bad, n_bad
+
+
+def restore_chunks(segments, chunk_bytes, buffer, crcs, chunk_ids, bad, skip_bad=False):
+    """Selective restore of the listed chunks (see orc_restore_chunks).  `bad` is a uint32 array
+    of n_chunks entries, updated in place for the listed chunks only.  Returns n_bad."""
+    L = lib()
+    buffer = _bytes_view(buffer)
+    crcs = np.ascontiguousarray(crcs, dtype=np.uint32)
+    views, ptrs, nbytes = _seg_tables(segments)
+    ids = np.ascontiguousarray(chunk_ids, dtype=np.uint64)
+    assert bad.dtype == np.uint32 and bad.size == crcs.size
+    u32p, u64p = ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint64)
+    return int(L.orc_restore_chunks(ptrs, nbytes.ctypes.data_as(u64p), len(views), chunk_bytes,
+                                    buffer.ctypes.data, crcs.ctypes.data_as(u32p),
+                                    ids.ctypes.data_as(u64p), ids.size,
+                                    bad.ctypes.data_as(u32p), 1 if skip_bad else 0))
 
 
 def f32_to_bf16(x):

@@ -188,6 +188,43 @@ uint64_t orc_restore(uint8_t *const *ptrs, const uint64_t *nbytes, uint64_t n_se
     return n_bad;
 }
 
+/* Copy buffer[lo:hi) (stream coordinates, hi <= payload) out to the segments it covers. */
+static void scatter_range(uint8_t *const *ptrs, const uint64_t *nbytes, uint64_t n_segs,
+                          const uint8_t *buffer, uint64_t lo, uint64_t hi)
+{
+    uint64_t off = 0;
+    for (uint64_t i = 0; i < n_segs; i++) {
+        uint64_t a = off, b = off + nbytes[i];
+        uint64_t s = a > lo ? a : lo, e = b < hi ? b : hi;
+        if (s < e)
+            memcpy(ptrs[i] + (s - a), buffer + s, e - s);
+        off = b;
+    }
+}
+
+/* Selective restore: verify only the listed chunks (bad[id] is written for them alone), and
+ * scatter the payload bytes of each listed chunk -- unless skip_bad is set and the chunk is
+ * bad, in which case its tensor ranges keep their old contents.  Returns the number of listed
+ * chunks that are bad. */
+uint64_t orc_restore_chunks(uint8_t *const *ptrs, const uint64_t *nbytes, uint64_t n_segs,
+                            uint64_t chunk_bytes, const uint8_t *buffer, const uint32_t *crcs,
+                            const uint64_t *ids, uint64_t n_ids, uint32_t *bad, int skip_bad)
+{
+    uint64_t payload = total_bytes(nbytes, n_segs), n_bad = 0;
+    for (uint64_t k = 0; k < n_ids; k++) {
+        uint64_t j = ids[k];
+        n_bad += orc_verify_chunks(buffer, crcs, chunk_bytes, bad, j, j + 1);
+        if (skip_bad && bad[j])
+            continue;
+        uint64_t lo = j * chunk_bytes, hi = (j + 1) * chunk_bytes;
+        if (hi > payload)
+            hi = payload;
+        if (lo < hi)
+            scatter_range(ptrs, nbytes, n_segs, buffer, lo, hi);
+    }
+    return n_bad;
+}
+
 /* ---- AdamW ----------------------------------------------------------------------------- */
 
 typedef struct {

@@ -18,11 +18,12 @@ FF_BF16, FF_F32 = 1, 2
 FF_KIND_RAW, FF_KIND_W16, FF_KIND_MASTER, FF_KIND_M, FF_KIND_V = 0, 1, 2, 3, 4
 FF_PLAN_HOST_ONLY = 1
 FF_RESTORE_VERIFY_ONLY = 1
+FF_RESTORE_SKIP_BAD = 2
 
 EXPORTS = ["ff_snapshot_plan", "ff_plan_destroy", "ff_plan_payload_bytes", "ff_plan_num_chunks",
            "ff_plan_buffer_bytes", "ff_plan_chunk_bytes", "ff_plan_num_segments",
-           "ff_plan_num_params", "ff_plan_layout_id", "ff_plan_segment_range", "ff_pack",
-           "ff_restore", "ff_adam_step_snapshot", "ff_crc32c", "ff_copy_ceiling", "ff_strerror"]
+           "ff_plan_num_params", "ff_plan_layout_id", "ff_plan_segment_range",
+           "ff_plan_chunk_span", "ff_pack", "ff_restore", "ff_restore_chunks", "ff_adam_step_snapshot", "ff_crc32c", "ff_copy_ceiling", "ff_strerror"]
 
 
 class ff_segment(ctypes.Structure):
@@ -67,6 +68,10 @@ def lib():
         L.ff_plan_layout_id.restype, L.ff_plan_layout_id.argtypes = u32, [vp]
         L.ff_plan_segment_range.restype = i32
         L.ff_plan_segment_range.argtypes = [vp, u64, ctypes.POINTER(u64), ctypes.POINTER(u64)]
+        L.ff_plan_chunk_span.restype = i32
+        L.ff_plan_chunk_span.argtypes = [vp, u64] + [ctypes.POINTER(u64)] * 4
+        L.ff_restore_chunks.restype = i32
+        L.ff_restore_chunks.argtypes = [vp, vp, vp, ctypes.POINTER(u64), u64, vp, vp, u32, vp]
         L.ff_pack.restype, L.ff_pack.argtypes = i32, [vp, vp, vp, vp]
         L.ff_restore.restype, L.ff_restore.argtypes = i32, [vp, vp, vp, vp, vp, u32, vp]
         L.ff_adam_step_snapshot.restype = i32
@@ -139,6 +144,12 @@ class Plan:
     num_params = property(lambda s: int(lib().ff_plan_num_params(s.handle)))
     layout_id = property(lambda s: int(lib().ff_plan_layout_id(s.handle)))
 
+    def chunk_span(self, chunk):
+        """(first_seg, n_seg, begin, end) of a chunk."""
+        v = [ctypes.c_uint64() for _ in range(4)]
+        _check(lib().ff_plan_chunk_span(self.handle, chunk, *[ctypes.byref(x) for x in v]))
+        return tuple(x.value for x in v)
+
     def segment_range(self, i):
         b, e = ctypes.c_uint64(), ctypes.c_uint64()
         _check(lib().ff_plan_segment_range(self.handle, i, ctypes.byref(b), ctypes.byref(e)))
@@ -176,6 +187,13 @@ def ff_pack(plan, chunks, crcs, stream=None):
 def ff_restore(plan, chunks, crcs, bad, n_bad, flags=0, stream=None):
     _check(lib().ff_restore(plan.handle, chunks.data_ptr(), crcs.data_ptr(), bad.data_ptr(),
                             n_bad.data_ptr(), flags, _stream_ptr(stream)))
+
+
+def ff_restore_chunks(plan, chunks, crcs, chunk_ids, bad, n_bad, flags=0, stream=None):
+    ids = (ctypes.c_uint64 * max(len(chunk_ids), 1))(*[int(c) for c in chunk_ids])
+    _check(lib().ff_restore_chunks(plan.handle, chunks.data_ptr(), crcs.data_ptr(), ids,
+                                   len(chunk_ids), bad.data_ptr(), n_bad.data_ptr(), flags,
+                                   _stream_ptr(stream)))
 
 
 def ff_adam_step_snapshot(plan, grads, hparams, chunks, crcs, stream=None):

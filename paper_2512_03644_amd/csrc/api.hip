@@ -1,6 +1,7 @@
 // extern "C" entry points of libffsnap.so (see include/ffsnap.h for the contract).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -28,6 +29,13 @@ struct ff_plan {
     uint32_t n_work = 0;
     uint64_t* grads = nullptr;        // [n_params] device copy of the caller's gradient pointers
     const uint32_t* fused_tabs = nullptr;
+    // selective restore: device lists of the chosen tiles / chunks
+    uint32_t* sel_tiles = nullptr;    // [n_tiles]
+    uint32_t* sel_chunks = nullptr;   // [n_chunks]
+    // Host staging of per-call tables: asynchronous copies read from here, so the caller's arrays
+    // are never touched after the call returns.  (One call at a time per plan.)
+    mutable std::vector<uint64_t> host_grads;
+    mutable std::vector<uint32_t> host_sel;
 };
 
 namespace {
@@ -69,7 +77,9 @@ int upload_tables(ff_plan* p)
     const uint64_t o_work = align_up(o_partial + L.n_tiles * 4, 256);
     const uint64_t o_grads = align_up(o_work + work.size() * sizeof(WorkTile), 256);
     const uint64_t o_ftabs = align_up(o_grads + L.params.size() * 8, 256);
-    const uint64_t total = align_up(o_ftabs + 2048 * 4, 256);
+    const uint64_t o_selt = align_up(o_ftabs + 2048 * 4, 256);
+    const uint64_t o_selc = align_up(o_selt + L.n_tiles * 4, 256);
+    const uint64_t total = align_up(o_selc + L.n_chunks * 4, 256);
 
     std::vector<unsigned char> host(total, 0);
     uint64_t* h_off = reinterpret_cast<uint64_t*>(host.data() + o_off);
@@ -102,6 +112,8 @@ int upload_tables(ff_plan* p)
     p->n_work = static_cast<uint32_t>(work.size());
     p->grads = reinterpret_cast<uint64_t*>(d + o_grads);
     p->fused_tabs = reinterpret_cast<const uint32_t*>(d + o_ftabs);
+    p->sel_tiles = reinterpret_cast<uint32_t*>(d + o_selt);
+    p->sel_chunks = reinterpret_cast<uint32_t*>(d + o_selc);
     return FF_OK;
 }
 
@@ -147,6 +159,7 @@ int ff_snapshot_plan(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_byt
     t.tile_rows = static_cast<uint32_t>(L.tile_bytes / 1024);
     t.lead_rows = 0;
     t.n_tiles = static_cast<uint32_t>(L.n_tiles);
+    t.tiles_per_chunk = L.tiles_per_chunk;
     fill_constants(t);
     // bits 16..18: bit 18 set = take bits 16..17 as the cache-hint selector (tuning knob)
     if (flags & 0x40000u) t.hint = (flags >> 16) & 3u;
@@ -208,21 +221,127 @@ int ff_pack(const ff_plan* p, void* chunks, uint32_t* crcs, void* hip_stream)
     return FF_OK;
 }
 
-int ff_restore(const ff_plan* p, const void* chunks, const uint32_t* crcs, uint32_t* bad,
-               uint64_t* n_bad, uint32_t flags, void* hip_stream)
+}  // extern "C"
+
+namespace {
+
+// Verify (and scatter) either every chunk or the chunks listed in the plan's selection tables.
+int restore_impl(const ff_plan* p, const void* chunks, const uint32_t* crcs, uint32_t* bad,
+                 uint64_t* n_bad, uint32_t flags, bool selected, uint32_t n_sel_chunks,
+                 hipStream_t s)
+{
+    const Layout& L = p->layout;
+    TileTables t = p->tables;
+    if (selected) {
+        t.tile_list = p->sel_tiles;
+        t.n_list = n_sel_chunks * L.tiles_per_chunk;
+    }
+    const uint32_t* chunk_list = selected ? p->sel_chunks : nullptr;
+    const uint64_t n_verify = selected ? n_sel_chunks : L.n_chunks;
+    void* buf = const_cast<void*>(chunks);
+    if (selected && n_sel_chunks == 0) {
+        FF_HIP_TRY(launch_zero_u64(n_bad, s));
+        return FF_OK;
+    }
+    const bool verify_only = (flags & FF_RESTORE_VERIFY_ONLY) != 0;
+    const bool skip_bad = (flags & FF_RESTORE_SKIP_BAD) != 0;
+    if (verify_only || skip_bad) {
+        // pass 1: read and fold only
+        FF_HIP_TRY(launch_tiles(kVerify, t, buf, n_bad, s));
+        FF_HIP_TRY(launch_combine_verify(t.partial, L.tiles_per_chunk, p->x_tile, p->affine,
+                                         n_verify, chunk_list, crcs, bad, n_bad, s));
+        if (verify_only) return FF_OK;
+        // pass 2: scatter the tiles of the chunks that verified
+        t.skip_bad = bad;
+        FF_HIP_TRY(launch_tiles(kRestore, t, buf, nullptr, s));
+        return FF_OK;
+    }
+    FF_HIP_TRY(launch_tiles(kRestore, t, buf, n_bad, s));
+    FF_HIP_TRY(launch_combine_verify(t.partial, L.tiles_per_chunk, p->x_tile, p->affine, n_verify,
+                                     chunk_list, crcs, bad, n_bad, s));
+    return FF_OK;
+}
+
+int check_restore_args(const ff_plan* p, const void* chunks, const uint32_t* crcs, uint32_t* bad,
+                       uint64_t* n_bad, uint32_t flags)
 {
     int rc = check_device_call(p);
     if (rc != FF_OK) return rc;
     if (!chunks || !crcs || !bad || !n_bad) return FF_ERR_NULL;
-    if (flags & ~FF_RESTORE_VERIFY_ONLY) return FF_ERR_INVALID;
+    if (flags & ~(FF_RESTORE_VERIFY_ONLY | FF_RESTORE_SKIP_BAD)) return FF_ERR_INVALID;
     if (reinterpret_cast<uint64_t>(chunks) % 16 || reinterpret_cast<uint64_t>(crcs) % 4 ||
         reinterpret_cast<uint64_t>(bad) % 4 || reinterpret_cast<uint64_t>(n_bad) % 8)
         return FF_ERR_INVALID;
+    return FF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ff_restore(const ff_plan* p, const void* chunks, const uint32_t* crcs, uint32_t* bad,
+               uint64_t* n_bad, uint32_t flags, void* hip_stream)
+{
+    int rc = check_restore_args(p, chunks, crcs, bad, n_bad, flags);
+    if (rc != FF_OK) return rc;
+    return restore_impl(p, chunks, crcs, bad, n_bad, flags, false, 0,
+                        static_cast<hipStream_t>(hip_stream));
+}
+
+int ff_restore_chunks(const ff_plan* p, const void* chunks, const uint32_t* crcs,
+                      const uint64_t* chunk_ids, uint64_t n_ids, uint32_t* bad, uint64_t* n_bad,
+                      uint32_t flags, void* hip_stream)
+{
+    int rc = check_restore_args(p, chunks, crcs, bad, n_bad, flags);
+    if (rc != FF_OK) return rc;
+    if (n_ids && !chunk_ids) return FF_ERR_NULL;
+    const Layout& L = p->layout;
+    if (n_ids > L.n_chunks) return FF_ERR_INVALID;
+    for (uint64_t k = 0; k < n_ids; k++) {
+        if (chunk_ids[k] >= L.n_chunks) return FF_ERR_INVALID;
+        if (k && chunk_ids[k] <= chunk_ids[k - 1]) return FF_ERR_INVALID;  // strictly ascending
+    }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const TileMode mode = (flags & FF_RESTORE_VERIFY_ONLY) ? kVerify : kRestore;
-    FF_HIP_TRY(launch_tiles(mode, p->tables, const_cast<void*>(chunks), n_bad, s));
-    FF_HIP_TRY(launch_combine_verify(p->tables.partial, p->layout.tiles_per_chunk, p->x_tile,
-                                     p->affine, p->layout.n_chunks, crcs, bad, n_bad, s));
+    const uint64_t tpc = L.tiles_per_chunk;
+    try {
+        p->host_sel.resize(n_ids * (tpc + 1));
+    } catch (const std::bad_alloc&) {
+        return FF_ERR_NOMEM;
+    }
+    uint32_t* h_chunks = p->host_sel.data();
+    uint32_t* h_tiles = h_chunks + n_ids;
+    for (uint64_t k = 0; k < n_ids; k++) {
+        h_chunks[k] = static_cast<uint32_t>(chunk_ids[k]);
+        for (uint64_t i = 0; i < tpc; i++)
+            h_tiles[k * tpc + i] = static_cast<uint32_t>(chunk_ids[k] * tpc + i);
+    }
+    if (n_ids) {
+        FF_HIP_TRY(hipMemcpyAsync(p->sel_chunks, h_chunks, n_ids * 4, hipMemcpyHostToDevice, s));
+        FF_HIP_TRY(hipMemcpyAsync(p->sel_tiles, h_tiles, n_ids * tpc * 4, hipMemcpyHostToDevice, s));
+    }
+    return restore_impl(p, chunks, crcs, bad, n_bad, flags, true, static_cast<uint32_t>(n_ids), s);
+}
+
+int ff_plan_chunk_span(const ff_plan* p, uint64_t chunk, uint64_t* first_seg, uint64_t* n_seg,
+                       uint64_t* begin, uint64_t* end)
+{
+    if (!p || !first_seg || !n_seg || !begin || !end) return FF_ERR_NULL;
+    const Layout& L = p->layout;
+    if (chunk >= L.n_chunks) return FF_ERR_INVALID;
+    const uint64_t lo = chunk * L.chunk_bytes;
+    const uint64_t hi = std::min(lo + L.chunk_bytes, L.payload);
+    // first segment whose end is beyond lo (segments are sorted by offset)
+    size_t a = 0, b = L.segs.size();
+    while (a < b) {
+        const size_t mid = (a + b) / 2;
+        if (L.segs[mid].off + L.segs[mid].nbytes <= lo) a = mid + 1; else b = mid;
+    }
+    size_t e = a;
+    while (e < L.segs.size() && L.segs[e].off < hi) e++;
+    *first_seg = a;
+    *n_seg = e - a;
+    *begin = lo;
+    *end = hi;
     return FF_OK;
 }
 
@@ -256,8 +375,15 @@ int ff_adam_step_snapshot(const ff_plan* p, const void* const* grads, const ff_a
         c.adam.eps = hp->eps;
     }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    // the pointer array is staged by the runtime before the call returns
-    FF_HIP_TRY(hipMemcpyAsync(p->grads, grads, L.params.size() * sizeof(uint64_t),
+    // the pointer array is copied into the plan first: the asynchronous upload reads from there
+    try {
+        p->host_grads.resize(L.params.size());
+    } catch (const std::bad_alloc&) {
+        return FF_ERR_NOMEM;
+    }
+    for (size_t i = 0; i < L.params.size(); i++)
+        p->host_grads[i] = reinterpret_cast<uint64_t>(grads[i]);
+    FF_HIP_TRY(hipMemcpyAsync(p->grads, p->host_grads.data(), L.params.size() * sizeof(uint64_t),
                               hipMemcpyHostToDevice, s));
     FF_HIP_TRY(launch_fused(p->work, p->n_work, p->grads, p->fused_tabs, chunks, crcs, L.n_chunks,
                             L.payload, L.buffer_bytes, p->affine, c, s));

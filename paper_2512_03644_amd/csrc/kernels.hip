@@ -175,8 +175,10 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
 
     const int lane = threadIdx.x & (kWaveSize - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
-    const uint32_t tile = blockIdx.x * kWavesPerBlock + wave;
-    if (tile >= T.n_tiles) return;
+    const uint32_t slot = blockIdx.x * kWavesPerBlock + wave;
+    if (slot >= (T.tile_list ? T.n_list : T.n_tiles)) return;
+    const uint32_t tile = T.tile_list ? __builtin_amdgcn_readfirstlane(T.tile_list[slot]) : slot;
+    if (T.skip_bad && __builtin_amdgcn_readfirstlane(T.skip_bad[tile / T.tiles_per_chunk])) return;
 
     // rows of this tile, as indices into the buffer's rows
     const int64_t g0 = static_cast<int64_t>(tile) * T.tile_rows - T.lead_rows;
@@ -348,12 +350,14 @@ __global__ void combine_pack_kernel(const uint32_t* __restrict__ partial, uint32
 
 __global__ void combine_verify_kernel(const uint32_t* __restrict__ partial,
                                       uint32_t tiles_per_chunk, uint32_t x_tile, uint32_t affine,
-                                      uint64_t n_chunks, const uint32_t* __restrict__ crcs,
+                                      uint64_t n_chunks, const uint32_t* __restrict__ chunk_list,
+                                      const uint32_t* __restrict__ crcs,
                                       uint32_t* __restrict__ bad, uint64_t* __restrict__ n_bad)
 {
-    const uint64_t j = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     bool is_bad = false;
-    if (j < n_chunks) {
+    if (i < n_chunks) {
+        const uint64_t j = chunk_list ? chunk_list[i] : i;
         const uint32_t crc =
             chunk_register(partial, j * tiles_per_chunk, tiles_per_chunk, x_tile) ^ affine;
         is_bad = (crc != crcs[j]);
@@ -377,6 +381,8 @@ __global__ void finish_crc_kernel(const uint32_t* __restrict__ partial, uint32_t
     }
     *out = c ^ affine;
 }
+
+__global__ void zero_u64_kernel(uint64_t* p) { *p = 0; }
 
 __global__ __launch_bounds__(256) void copy_kernel(u32x4* __restrict__ dst,
                                                    const u32x4* __restrict__ src, uint64_t n16)
@@ -417,8 +423,9 @@ static void launch_tiles_hint(int hint, dim3 grid, dim3 block, hipStream_t strea
 hipError_t launch_tiles(TileMode mode, const TileTables& t, void* chunks, uint64_t* n_bad,
                         hipStream_t stream)
 {
-    if (t.n_tiles == 0) return hipSuccess;
-    const dim3 grid((t.n_tiles + kWavesPerBlock - 1) / kWavesPerBlock);
+    const uint32_t count = t.tile_list ? t.n_list : t.n_tiles;
+    if (count == 0) return hipSuccess;
+    const dim3 grid((count + kWavesPerBlock - 1) / kWavesPerBlock);
     const dim3 block(kWaveSize * kWavesPerBlock);
     uint8_t* c = static_cast<uint8_t*>(chunks);
     switch (mode) {
@@ -442,13 +449,14 @@ hipError_t launch_combine_pack(const uint32_t* partial, uint32_t tiles_per_chunk
 
 hipError_t launch_combine_verify(const uint32_t* partial, uint32_t tiles_per_chunk,
                                  uint32_t x_tile, uint32_t affine, uint64_t n_chunks,
-                                 const uint32_t* crcs, uint32_t* bad, uint64_t* n_bad,
-                                 hipStream_t stream)
+                                 const uint32_t* chunk_list, const uint32_t* crcs, uint32_t* bad,
+                                 uint64_t* n_bad, hipStream_t stream)
 {
+    if (n_chunks == 0) return hipSuccess;
     const unsigned block = 256;
     const unsigned grid = static_cast<unsigned>((n_chunks + block - 1) / block);
     hipLaunchKernelGGL(combine_verify_kernel, dim3(grid), dim3(block), 0, stream, partial,
-                       tiles_per_chunk, x_tile, affine, n_chunks, crcs, bad, n_bad);
+                       tiles_per_chunk, x_tile, affine, n_chunks, chunk_list, crcs, bad, n_bad);
     return hipGetLastError();
 }
 
@@ -458,6 +466,12 @@ hipError_t launch_finish_crc(const uint32_t* partial, uint32_t n_tiles, uint32_t
 {
     hipLaunchKernelGGL(finish_crc_kernel, dim3(1), dim3(64), 0, stream, partial, n_tiles, x_tile,
                        tail, tail_bytes, affine, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_zero_u64(uint64_t* p, hipStream_t stream)
+{
+    hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, stream, p);
     return hipGetLastError();
 }
 

@@ -22,6 +22,11 @@ struct TileTables {
     uint32_t x32 = 0;                         // x^32 mod P
     uint32_t z[6] = {0, 0, 0, 0, 0, 0};       // x^(128 * 2^l) mod P
     uint32_t hint = 3;                        // bit 0: non-temporal tensor-side accesses, bit 1: buffer-side
+    // selective restore
+    const uint32_t* tile_list = nullptr;      // if set: the n_list tiles to process
+    uint32_t n_list = 0;
+    const uint32_t* skip_bad = nullptr;       // if set: bad[] per chunk; tiles of bad chunks are left out
+    uint32_t tiles_per_chunk = 1;
 };
 
 enum TileMode { kPack = 0, kRestore = 1, kVerify = 2 };
@@ -37,17 +42,20 @@ hipError_t launch_combine_pack(const uint32_t* partial, uint32_t tiles_per_chunk
                                uint32_t affine, uint64_t n_chunks, uint32_t* crcs,
                                hipStream_t stream);
 
-// bad[j] = (recomputed CRC != crcs[j]); *n_bad += number of bad chunks.
+// bad[j] = (recomputed CRC != crcs[j]); *n_bad += number of bad chunks.  With chunk_list set,
+// only the n_chunks chunks it names are looked at.
 hipError_t launch_combine_verify(const uint32_t* partial, uint32_t tiles_per_chunk,
                                  uint32_t x_tile, uint32_t affine, uint64_t n_chunks,
-                                 const uint32_t* crcs, uint32_t* bad, uint64_t* n_bad,
-                                 hipStream_t stream);
+                                 const uint32_t* chunk_list, const uint32_t* crcs, uint32_t* bad,
+                                 uint64_t* n_bad, hipStream_t stream);
 
 // CRC of one buffer: combine n_tiles registers, then run the register over `tail_bytes` more
 // bytes at `tail`, then apply the preset/complement term `affine`.
 hipError_t launch_finish_crc(const uint32_t* partial, uint32_t n_tiles, uint32_t x_tile,
                              const uint8_t* tail, uint32_t tail_bytes, uint32_t affine,
                              uint32_t* out, hipStream_t stream);
+
+hipError_t launch_zero_u64(uint64_t* p, hipStream_t stream);
 
 hipError_t launch_copy(void* dst, const void* src, uint64_t nbytes, hipStream_t stream);
 

@@ -308,3 +308,76 @@ def test_fused_adam_argument_errors():
     with pytest.raises(ff.FFError) as e:
         ff.ff_adam_step_snapshot(raw, [p.grad], HP, chunks, crcs)
     assert e.value.status == ff.FF_ERR_INVALID
+
+
+# ---- selective restore ------------------------------------------------------------------------------
+
+def _segments_as_stream(shard):
+    return np.concatenate(_host_segments(shard)[0])
+
+
+@pytest.mark.parametrize("chunk,tile_log2", [(1024, 0), (1 << 14, 12), (1 << 16, 0), (1 << 20, 0)])
+def test_restore_chunks_matches_oracle(oracle, chunk, tile_log2):
+    numels = [int(x) for x in np.random.default_rng(chunk + 1).integers(1, 60000, size=30)]
+    shard = wl.param_shard("sel", numels, chunk, 31, DEV, tiny_recipe=True)
+    plan, chunks, crcs, bad, n_bad, want_buf, want_crcs = _pack_and_compare(shard, oracle, tile_log2)
+    n = plan.num_chunks
+    rng = np.random.default_rng(7)
+    ids = sorted({int(x) for x in rng.integers(0, n, size=max(2, n // 3))} | {0, n - 1})
+    dirty = chunks.clone()
+    flipped = ids[len(ids) // 2]
+    dirty[flipped * chunk + 5] ^= 0x40                       # one listed chunk is corrupt
+    other = next(j for j in range(n) if j not in ids)
+    dirty[other * chunk + 9] ^= 0x01                         # an unlisted one too: must go unnoticed
+    for flags, skip in ((0, False), (ff.FF_RESTORE_SKIP_BAD, True)):
+        _poison_segments(shard)
+        bad.fill_(7)
+        n_bad.fill_(99)
+        ff.ff_restore_chunks(plan, dirty, crcs, ids, bad, n_bad, flags=flags)
+        torch.cuda.synchronize()
+        # the oracle on host copies poisoned the same way
+        host = [np.full(h.size, 0xA5, dtype=np.uint8) for h in _host_segments(shard)[0]]
+        want_bad = np.full(n, 7, dtype=np.uint32)
+        want_n = oracle.restore_chunks(host, chunk, dirty.cpu().numpy(), want_crcs, ids, want_bad,
+                                       skip_bad=skip)
+        assert want_n == 1
+        assert int(n_bad.item()) == want_n
+        assert np.array_equal(_u32(bad), want_bad)
+        assert np.array_equal(_segments_as_stream(shard), np.concatenate(host))
+    # an empty list only clears n_bad
+    n_bad.fill_(5)
+    ff.ff_restore_chunks(plan, dirty, crcs, [], bad, n_bad)
+    torch.cuda.synchronize()
+    assert int(n_bad.item()) == 0
+    L = ff.lib()
+    import ctypes
+    two = (ctypes.c_uint64 * 2)(3, 3)
+    assert L.ff_restore_chunks(plan.handle, dirty.data_ptr(), crcs.data_ptr(), two, 2,
+                               bad.data_ptr(), n_bad.data_ptr(), 0, None) == ff.FF_ERR_INVALID
+    two = (ctypes.c_uint64 * 2)(0, n)
+    assert L.ff_restore_chunks(plan.handle, dirty.data_ptr(), crcs.data_ptr(), two, 2,
+                               bad.data_ptr(), n_bad.data_ptr(), 0, None) == ff.FF_ERR_INVALID
+
+
+def test_full_restore_skip_bad_on_ragged_layout(oracle):
+    lay = wl.fragmented_layout(seed=4, n_tensors=1500, mu=6.0, sigma=2.0, max_numel=1 << 16)
+    shard = wl.fragmented_shard(lay, 1 << 14, seed=4, device=DEV)
+    plan, chunks, crcs, bad, n_bad, want_buf, want_crcs = _pack_and_compare(shard, oracle)
+    n, C = plan.num_chunks, shard.chunk_bytes
+    hits = wl.corrupt_chunks(n, C, seed=4, fraction=0.05)
+    dirty = chunks.clone()
+    for c, off, bit in hits:
+        dirty[c * C + off] ^= (1 << bit)
+    before = shard.arena.clone()
+    _poison_segments(shard)
+    poisoned = shard.arena.cpu().numpy().copy()
+    ff.ff_restore(plan, dirty, crcs, bad, n_bad, flags=ff.FF_RESTORE_SKIP_BAD)
+    torch.cuda.synchronize()
+    arena = poisoned.copy()
+    host = [arena[o:o + nb] for o, nb in shard.spans]
+    want_bad = np.zeros(n, dtype=np.uint32)
+    want_n = oracle.restore_chunks(host, C, dirty.cpu().numpy(), want_crcs, np.arange(n), want_bad,
+                                   skip_bad=True)
+    assert want_n == len(hits) and int(n_bad.item()) == want_n
+    assert np.array_equal(_u32(bad), want_bad)
+    assert np.array_equal(shard.arena.cpu().numpy(), arena)   # gaps and skipped ranges untouched

@@ -136,3 +136,22 @@ def test_fold_relations_are_multiples_of_the_generator(oracle):
                 assert 0 <= e < NE and 0 <= c < NF
                 acc ^= oracle.crc_shift(0x80000000, 4 * (S * e + c))
             assert acc == 0
+
+
+def test_chunk_span_names_the_segments_a_chunk_covers():
+    rng = np.random.default_rng(12)
+    sizes = [int(x) for x in rng.integers(1, 900, size=40)]
+    tensors = [torch.zeros(n, dtype=torch.float32 if i % 2 else torch.bfloat16)
+               for i, n in enumerate(sizes)]
+    C = 1024
+    plan = _host_plan(tensors, C)
+    ranges = [plan.segment_range(i) for i in range(plan.num_segments)]
+    for j in range(plan.num_chunks):
+        first, n, begin, end = plan.chunk_span(j)
+        assert begin == j * C and end == min((j + 1) * C, plan.payload_bytes)
+        want = [i for i, (b, e) in enumerate(ranges) if b < end and e > begin]
+        assert list(range(first, first + n)) == want
+    L = ff.lib()
+    z = [ctypes.c_uint64() for _ in range(4)]
+    assert L.ff_plan_chunk_span(plan.handle, plan.num_chunks, *[ctypes.byref(x) for x in z]) \
+        == ff.FF_ERR_INVALID

@@ -130,3 +130,70 @@ def test_swapped_chunks_are_detected(oracle):
     sw[0:C], sw[C:2 * C] = buf[C:2 * C], buf[0:C]
     bad, n_bad = oracle.verify(sw, crcs, C)
     assert n_bad == 2 and bad[0] == 1 and bad[1] == 1
+
+
+# ---- selective restore ------------------------------------------------------------------------------
+
+def _poison(segs):
+    for s in segs:
+        s.view(np.uint8)[...] = 0xA5
+
+
+def _stream(segs):
+    return np.concatenate([s.view(np.uint8).reshape(-1) for s in segs])
+
+
+def test_restore_chunks_of_all_chunks_is_restore(oracle):
+    shard = _small_param_shard(chunk=2048, seed=21)
+    segs = _np_segments(shard)
+    buf, crcs = oracle.pack(segs, shard.chunk_bytes)
+    n = shard.num_chunks
+    _poison(segs)
+    bad = np.full(n, 7, dtype=np.uint32)
+    assert oracle.restore_chunks(segs, shard.chunk_bytes, buf, crcs, np.arange(n), bad) == 0
+    assert not bad.any()
+    assert np.array_equal(_stream(segs), buf[:shard.payload_bytes])
+
+
+def test_restore_chunks_touches_only_the_listed_chunks(oracle):
+    shard = _small_param_shard(chunk=1024, seed=22)
+    segs = _np_segments(shard)
+    buf, crcs = oracle.pack(segs, shard.chunk_bytes)
+    n, C, N = shard.num_chunks, shard.chunk_bytes, shard.payload_bytes
+    ids = np.array([1, 4, n - 1], dtype=np.uint64)
+    _poison(segs)
+    bad = np.full(n, 7, dtype=np.uint32)
+    assert oracle.restore_chunks(segs, C, buf, crcs, ids, bad) == 0
+    got = _stream(segs)
+    inside = np.zeros(N, dtype=bool)
+    for j in ids:
+        inside[int(j) * C:min((int(j) + 1) * C, N)] = True
+    assert np.array_equal(got[inside], buf[:N][inside])
+    assert np.all(got[~inside] == 0xA5)                     # everything else keeps the poison
+    assert np.all(bad[ids.astype(int)] == 0)
+    assert np.all(np.delete(bad, ids.astype(int)) == 7)     # unlisted entries of bad[] untouched
+
+
+def test_restore_chunks_skip_bad(oracle):
+    shard = _small_param_shard(chunk=1024, seed=23)
+    segs = _np_segments(shard)
+    buf, crcs = oracle.pack(segs, shard.chunk_bytes)
+    n, C, N = shard.num_chunks, shard.chunk_bytes, shard.payload_bytes
+    dirty = buf.copy()
+    dirty[2 * C + 17] ^= 0x10
+    dirty[5 * C + 900] ^= 0x01
+    ids = np.array([0, 2, 3, 5], dtype=np.uint64)
+    for skip in (False, True):
+        _poison(segs)
+        bad = np.zeros(n, dtype=np.uint32)
+        assert oracle.restore_chunks(segs, C, dirty, crcs, ids, bad, skip_bad=skip) == 2
+        assert list(np.nonzero(bad)[0]) == [2, 5]
+        got = _stream(segs)
+        for j in (0, 3):
+            assert np.array_equal(got[j * C:(j + 1) * C], dirty[j * C:(j + 1) * C])
+        for j in (2, 5):
+            piece = got[j * C:min((j + 1) * C, N)]
+            if skip:
+                assert np.all(piece == 0xA5)               # destinations left as they were
+            else:
+                assert np.array_equal(piece, dirty[j * C:min((j + 1) * C, N)])
