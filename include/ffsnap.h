@@ -117,6 +117,33 @@ uint32_t ff_plan_layout_id(const ff_plan *plan);
 int ff_plan_segment_range(const ff_plan *plan, uint64_t i, uint64_t *begin, uint64_t *end);
 
 /*
+ * Checkpoint razor (section 4.2): which of a worker's segments are unique state, to be
+ * snapshotted every iteration, and which are redundant across the data-parallel group, to be
+ * saved only at recovery time by one healthy worker ("lazy backup").  The two rules:
+ *   (1) data-parallel degree > 1                                  -> model weights are redundant;
+ *   (2) data-parallel degree > 1 and no distributed optimizer     -> optimizer states are redundant.
+ * FF_KIND_W16 segments are the model weights, FF_KIND_MASTER / M / V the optimizer states (the
+ * 12 bytes per parameter of the paper's size law); FF_KIND_RAW segments have no known role and
+ * always count as unique.  Host-only; no GPU is touched.
+ */
+typedef struct {
+    uint32_t dp_degree;             /* d >= 1 */
+    uint32_t distributed_optimizer; /* 0 / 1: optimizer states sharded over the DP group */
+} ff_razor_config;
+
+#define FF_RAZOR_UNIQUE 0u    /* the per-iteration snapshot list */
+#define FF_RAZOR_REDUNDANT 1u /* the lazy-backup list (the complement) */
+
+/*
+ * Writes to out_indices (HOST, room for n_segs entries) the indices, ascending, of the segments
+ * of segs[] (HOST) that fall into `which`, and their number to *n_out.  A plan for the selection
+ * is then built from those segments in that order.  FF_ERR_NULL / FF_ERR_INVALID (dp_degree 0,
+ * unknown `which`, kind or flag value) as usual.
+ */
+int ff_razor_select(const ff_segment *segs, uint64_t n_segs, const ff_razor_config *cfg,
+                    uint32_t which, uint64_t *out_indices, uint64_t *n_out);
+
+/*
  * Snapshot (section 4.2, "fast snapshot"): gather the segments into `chunks` and write one
  * CRC32C per chunk.  chunks: DEVICE, 16-byte aligned, ff_plan_buffer_bytes() bytes, every byte
  * of it is written (the tail of the last chunk with zeros).  crcs: DEVICE, num_chunks uint32.

@@ -245,3 +245,20 @@ def adam_snapshot(params, grads_bf16, segments, chunk_bytes, hparams, threads=1)
     for (w16, master, m, v), g in zip(params, grads_bf16):
         adam_f32(g, master, m, v, w16, **hparams)
     return pack(segments, chunk_bytes, threads=threads)
+
+
+def razor_unique(kinds, dp_degree, distributed_optimizer):
+    """Checkpoint razor (section 4.2), written out as its truth table.  kinds: 'raw', 'weight',
+    'optimizer' per segment.  Returns the indices of the unique segments; the rest is redundant.
+      rule 1: d > 1                              -> weights redundant
+      rule 2: d > 1 and no distributed optimizer -> optimizer states redundant"""
+    table = {
+        # (d > 1, distributed optimizer): (weights unique, optimizer states unique)
+        (False, False): (True, True),
+        (False, True): (True, True),
+        (True, False): (False, False),
+        (True, True): (False, True),
+    }
+    w_unique, o_unique = table[(dp_degree > 1, bool(distributed_optimizer))]
+    keep = {"raw": True, "weight": w_unique, "optimizer": o_unique}
+    return [i for i, k in enumerate(kinds) if keep[k]]

@@ -23,7 +23,7 @@ FF_RESTORE_SKIP_BAD = 2
 EXPORTS = ["ff_snapshot_plan", "ff_plan_destroy", "ff_plan_payload_bytes", "ff_plan_num_chunks",
            "ff_plan_buffer_bytes", "ff_plan_chunk_bytes", "ff_plan_num_segments",
            "ff_plan_num_params", "ff_plan_layout_id", "ff_plan_segment_range",
-           "ff_plan_chunk_span", "ff_pack", "ff_restore", "ff_restore_chunks", "ff_adam_step_snapshot", "ff_crc32c", "ff_copy_ceiling", "ff_strerror"]
+           "ff_plan_chunk_span", "ff_razor_select", "ff_pack", "ff_restore", "ff_restore_chunks", "ff_adam_step_snapshot", "ff_crc32c", "ff_copy_ceiling", "ff_strerror"]
 
 
 class ff_segment(ctypes.Structure):
@@ -36,6 +36,13 @@ class ff_adam_hparams(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
                 ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float),
                 ("step", ctypes.c_uint32)]
+
+
+class ff_razor_config(ctypes.Structure):
+    _fields_ = [("dp_degree", ctypes.c_uint32), ("distributed_optimizer", ctypes.c_uint32)]
+
+
+FF_RAZOR_UNIQUE, FF_RAZOR_REDUNDANT = 0, 1
 
 
 class FFError(RuntimeError):
@@ -72,6 +79,10 @@ def lib():
         L.ff_plan_chunk_span.argtypes = [vp, u64] + [ctypes.POINTER(u64)] * 4
         L.ff_restore_chunks.restype = i32
         L.ff_restore_chunks.argtypes = [vp, vp, vp, ctypes.POINTER(u64), u64, vp, vp, u32, vp]
+        L.ff_razor_select.restype = i32
+        L.ff_razor_select.argtypes = [ctypes.POINTER(ff_segment), u64,
+                                      ctypes.POINTER(ff_razor_config), u32, ctypes.POINTER(u64),
+                                      ctypes.POINTER(u64)]
         L.ff_pack.restype, L.ff_pack.argtypes = i32, [vp, vp, vp, vp]
         L.ff_restore.restype, L.ff_restore.argtypes = i32, [vp, vp, vp, vp, vp, u32, vp]
         L.ff_adam_step_snapshot.restype = i32
@@ -178,6 +189,15 @@ def plan_for_shard(shard, flags=0, tile_log2=0):
     else:
         kinds, pids = [FF_KIND_RAW] * len(shard.segments), [0] * len(shard.segments)
     return ff_snapshot_plan(shard.segments, shard.chunk_bytes, flags, kinds, pids, tile_log2)
+
+
+def ff_razor_select(segs, n_segs, dp_degree, distributed_optimizer, which=FF_RAZOR_UNIQUE):
+    """Indices of the unique (or redundant) segments of an ff_segment array."""
+    cfg = ff_razor_config(dp_degree, 1 if distributed_optimizer else 0)
+    out = (ctypes.c_uint64 * max(n_segs, 1))()
+    n = ctypes.c_uint64()
+    _check(lib().ff_razor_select(segs, n_segs, ctypes.byref(cfg), which, out, ctypes.byref(n)))
+    return [int(out[i]) for i in range(n.value)]
 
 
 def ff_pack(plan, chunks, crcs, stream=None):

@@ -207,6 +207,31 @@ int ff_plan_segment_range(const ff_plan* p, uint64_t i, uint64_t* begin, uint64_
     return FF_OK;
 }
 
+int ff_razor_select(const ff_segment* segs, uint64_t n_segs, const ff_razor_config* cfg,
+                    uint32_t which, uint64_t* out_indices, uint64_t* n_out)
+{
+    if ((n_segs && !segs) || !cfg || !out_indices || !n_out) return FF_ERR_NULL;
+    if (cfg->dp_degree == 0 || cfg->distributed_optimizer > 1 || which > FF_RAZOR_REDUNDANT)
+        return FF_ERR_INVALID;
+    const bool weights_redundant = cfg->dp_degree > 1;                                 // rule 1
+    const bool optimizer_redundant = cfg->dp_degree > 1 && !cfg->distributed_optimizer;  // rule 2
+    uint64_t n = 0;
+    for (uint64_t i = 0; i < n_segs; i++) {
+        bool redundant;
+        switch (segs[i].kind) {
+        case FF_KIND_RAW: redundant = false; break;
+        case FF_KIND_W16: redundant = weights_redundant; break;
+        case FF_KIND_MASTER:
+        case FF_KIND_M:
+        case FF_KIND_V: redundant = optimizer_redundant; break;
+        default: return FF_ERR_INVALID;
+        }
+        if (redundant == (which == FF_RAZOR_REDUNDANT)) out_indices[n++] = i;
+    }
+    *n_out = n;
+    return FF_OK;
+}
+
 int ff_pack(const ff_plan* p, void* chunks, uint32_t* crcs, void* hip_stream)
 {
     int rc = check_device_call(p);

@@ -155,3 +155,38 @@ def test_chunk_span_names_the_segments_a_chunk_covers():
     z = [ctypes.c_uint64() for _ in range(4)]
     assert L.ff_plan_chunk_span(plan.handle, plan.num_chunks, *[ctypes.byref(x) for x in z]) \
         == ff.FF_ERR_INVALID
+
+
+def test_checkpoint_razor_rules_and_size_law(oracle):
+    shard = wl.param_shard("s", [1000, 77, 4096], 4096, 3, "cpu")
+    raw = torch.zeros(10, dtype=torch.float32)
+    tensors = [raw] + shard.segments
+    kinds = [ff.FF_KIND_RAW] + [ff.FF_KIND_W16, ff.FF_KIND_MASTER, ff.FF_KIND_M, ff.FF_KIND_V] * 3
+    names = {ff.FF_KIND_RAW: "raw", ff.FF_KIND_W16: "weight", ff.FF_KIND_MASTER: "optimizer",
+             ff.FF_KIND_M: "optimizer", ff.FF_KIND_V: "optimizer"}
+    segs = ff.make_segments(tensors, kinds, [0] + [p for p in range(3) for _ in range(4)])
+    n_el = sum(p.master.numel() for p in shard.params)
+    for d in (1, 2, 8, 64):
+        for dist in (False, True):
+            uniq = ff.ff_razor_select(segs, len(tensors), d, dist, ff.FF_RAZOR_UNIQUE)
+            red = ff.ff_razor_select(segs, len(tensors), d, dist, ff.FF_RAZOR_REDUNDANT)
+            assert uniq == oracle.razor_unique([names[k] for k in kinds], d, dist)
+            assert sorted(uniq + red) == list(range(len(tensors))) and not set(uniq) & set(red)
+            nbytes = sum(tensors[i].numel() * tensors[i].element_size() for i in uniq) - 40
+            if d == 1:
+                assert nbytes == 14 * n_el
+            elif dist:
+                assert nbytes == 12 * n_el      # the paper's 12*phi/d per worker
+            else:
+                assert nbytes == 0
+            if uniq:
+                plan = _host_plan([tensors[i] for i in uniq], 4096)
+                assert plan.payload_bytes == nbytes + 40
+    L = ff.lib()
+    out = (ctypes.c_uint64 * 16)()
+    n = ctypes.c_uint64()
+    bad_cfg = ff.ff_razor_config(0, 0)
+    assert L.ff_razor_select(segs, 13, ctypes.byref(bad_cfg), 0, out, ctypes.byref(n)) == ff.FF_ERR_INVALID
+    ok_cfg = ff.ff_razor_config(2, 1)
+    assert L.ff_razor_select(segs, 13, ctypes.byref(ok_cfg), 2, out, ctypes.byref(n)) == ff.FF_ERR_INVALID
+    assert L.ff_razor_select(segs, 13, None, 0, out, ctypes.byref(n)) == ff.FF_ERR_NULL
