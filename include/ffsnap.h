@@ -151,6 +151,22 @@ int ff_razor_select(const ff_segment *segs, uint64_t n_segs, const ff_razor_conf
 int ff_pack(const ff_plan *plan, void *chunks, uint32_t *crcs, void *hip_stream);
 
 /*
+ * Snapshot into host memory (section 4.2: the snapshot is copied device-to-host into a
+ * pre-allocated buffer, from where it is streamed to the next worker).  The snapshot is packed
+ * in slices of slice_chunks chunks on pack_stream; as soon as a slice and its CRCs are complete
+ * they are copied to host_chunks / host_crcs on copy_stream, while the next slice is being
+ * packed.  chunks / crcs: DEVICE staging of the full snapshot, as for ff_pack (it also holds the
+ * snapshot afterwards).  host_chunks (buffer_bytes) and host_crcs (num_chunks uint32): HOST,
+ * ideally pinned (hipHostMalloc); pageable memory works but the copies then do not overlap.
+ * The two streams should differ (both default priority); the call returns without
+ * synchronising: the host buffers are complete once copy_stream has been synchronised.  Keeping
+ * the two most recent snapshots (section 4.2) is the caller alternating two host buffers.
+ */
+int ff_pack_to_host(const ff_plan *plan, void *chunks, uint32_t *crcs, void *host_chunks,
+                    uint32_t *host_crcs, uint64_t slice_chunks, void *pack_stream,
+                    void *copy_stream);
+
+/*
  * State loading on failover (section 3.1 steps 5-6, section 3.3): recompute the CRC32C of every
  * chunk of `chunks`, set bad[j] = (recomputed != crcs[j]) and *n_bad = sum(bad), and copy every
  * segment's bytes out of the buffer into the plan's tensors -- from good and bad chunks alike:

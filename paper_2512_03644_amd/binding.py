@@ -23,7 +23,7 @@ FF_RESTORE_SKIP_BAD = 2
 EXPORTS = ["ff_snapshot_plan", "ff_plan_destroy", "ff_plan_payload_bytes", "ff_plan_num_chunks",
            "ff_plan_buffer_bytes", "ff_plan_chunk_bytes", "ff_plan_num_segments",
            "ff_plan_num_params", "ff_plan_layout_id", "ff_plan_segment_range",
-           "ff_plan_chunk_span", "ff_razor_select", "ff_pack", "ff_restore", "ff_restore_chunks", "ff_adam_step_snapshot", "ff_crc32c", "ff_copy_ceiling", "ff_strerror"]
+           "ff_plan_chunk_span", "ff_razor_select", "ff_pack", "ff_pack_to_host", "ff_restore", "ff_restore_chunks", "ff_adam_step_snapshot", "ff_crc32c", "ff_copy_ceiling", "ff_strerror"]
 
 
 class ff_segment(ctypes.Structure):
@@ -84,6 +84,8 @@ def lib():
                                       ctypes.POINTER(ff_razor_config), u32, ctypes.POINTER(u64),
                                       ctypes.POINTER(u64)]
         L.ff_pack.restype, L.ff_pack.argtypes = i32, [vp, vp, vp, vp]
+        L.ff_pack_to_host.restype = i32
+        L.ff_pack_to_host.argtypes = [vp, vp, vp, vp, vp, u64, vp, vp]
         L.ff_restore.restype, L.ff_restore.argtypes = i32, [vp, vp, vp, vp, vp, u32, vp]
         L.ff_adam_step_snapshot.restype = i32
         L.ff_adam_step_snapshot.argtypes = [vp, ctypes.POINTER(vp),
@@ -202,6 +204,14 @@ def ff_razor_select(segs, n_segs, dp_degree, distributed_optimizer, which=FF_RAZ
 
 def ff_pack(plan, chunks, crcs, stream=None):
     _check(lib().ff_pack(plan.handle, chunks.data_ptr(), crcs.data_ptr(), _stream_ptr(stream)))
+
+
+def ff_pack_to_host(plan, chunks, crcs, host_chunks, host_crcs, slice_chunks, pack_stream,
+                    copy_stream):
+    """host_chunks / host_crcs: CPU tensors (pinned for overlap)."""
+    _check(lib().ff_pack_to_host(plan.handle, chunks.data_ptr(), crcs.data_ptr(),
+                                 host_chunks.data_ptr(), host_crcs.data_ptr(), slice_chunks,
+                                 _stream_ptr(pack_stream), _stream_ptr(copy_stream)))
 
 
 def ff_restore(plan, chunks, crcs, bad, n_bad, flags=0, stream=None):

@@ -34,6 +34,7 @@ struct ff_plan {
     uint32_t* sel_chunks = nullptr;   // [n_chunks]
     // Host staging of per-call tables: asynchronous copies read from here, so the caller's arrays
     // are never touched after the call returns.  (One call at a time per plan.)
+    mutable std::vector<hipEvent_t> events;  // one per slice of ff_pack_to_host, created on demand
     mutable std::vector<uint64_t> host_grads;
     mutable std::vector<uint32_t> host_sel;
 };
@@ -186,6 +187,7 @@ int ff_snapshot_plan(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_byt
 void ff_plan_destroy(ff_plan* plan)
 {
     if (!plan) return;
+    for (hipEvent_t e : plan->events) (void)hipEventDestroy(e);
     if (plan->dev_block) (void)hipFree(plan->dev_block);
     delete plan;
 }
@@ -303,6 +305,49 @@ int check_restore_args(const ff_plan* p, const void* chunks, const uint32_t* crc
 }  // namespace
 
 extern "C" {
+
+int ff_pack_to_host(const ff_plan* p, void* chunks, uint32_t* crcs, void* host_chunks,
+                    uint32_t* host_crcs, uint64_t slice_chunks, void* pack_stream,
+                    void* copy_stream)
+{
+    int rc = check_device_call(p);
+    if (rc != FF_OK) return rc;
+    if (!chunks || !crcs || !host_chunks || !host_crcs) return FF_ERR_NULL;
+    if (reinterpret_cast<uint64_t>(chunks) % 16 || reinterpret_cast<uint64_t>(crcs) % 4 ||
+        slice_chunks == 0)
+        return FF_ERR_INVALID;
+    const Layout& L = p->layout;
+    hipStream_t ps = static_cast<hipStream_t>(pack_stream);
+    hipStream_t cs = static_cast<hipStream_t>(copy_stream);
+    const uint64_t n_slices = (L.n_chunks + slice_chunks - 1) / slice_chunks;
+    try {
+        while (p->events.size() < n_slices) {
+            hipEvent_t e;
+            FF_HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+            p->events.push_back(e);
+        }
+    } catch (const std::bad_alloc&) {
+        return FF_ERR_NOMEM;
+    }
+    uint8_t* d = static_cast<uint8_t*>(chunks);
+    uint8_t* h = static_cast<uint8_t*>(host_chunks);
+    for (uint64_t k = 0; k < n_slices; k++) {
+        const uint64_t j0 = k * slice_chunks;
+        const uint64_t nj = std::min(slice_chunks, L.n_chunks - j0);
+        TileTables t = p->tables;
+        t.tile_begin = static_cast<uint32_t>(j0 * L.tiles_per_chunk);
+        t.n_list = static_cast<uint32_t>(nj * L.tiles_per_chunk);
+        FF_HIP_TRY(launch_tiles(kPack, t, chunks, nullptr, ps));
+        FF_HIP_TRY(launch_combine_pack(t.partial + j0 * L.tiles_per_chunk, L.tiles_per_chunk,
+                                       p->x_tile, p->affine, nj, crcs + j0, ps));
+        FF_HIP_TRY(hipEventRecord(p->events[k], ps));
+        FF_HIP_TRY(hipStreamWaitEvent(cs, p->events[k], 0));
+        FF_HIP_TRY(hipMemcpyAsync(h + j0 * L.chunk_bytes, d + j0 * L.chunk_bytes,
+                                  nj * L.chunk_bytes, hipMemcpyDeviceToHost, cs));
+        FF_HIP_TRY(hipMemcpyAsync(host_crcs + j0, crcs + j0, nj * 4, hipMemcpyDeviceToHost, cs));
+    }
+    return FF_OK;
+}
 
 int ff_restore(const ff_plan* p, const void* chunks, const uint32_t* crcs, uint32_t* bad,
                uint64_t* n_bad, uint32_t flags, void* hip_stream)

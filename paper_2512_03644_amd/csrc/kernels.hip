@@ -176,8 +176,9 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
     const int lane = threadIdx.x & (kWaveSize - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
     const uint32_t slot = blockIdx.x * kWavesPerBlock + wave;
-    if (slot >= (T.tile_list ? T.n_list : T.n_tiles)) return;
-    const uint32_t tile = T.tile_list ? __builtin_amdgcn_readfirstlane(T.tile_list[slot]) : slot;
+    if (slot >= (T.n_list ? T.n_list : T.n_tiles)) return;
+    const uint32_t tile = T.tile_list ? __builtin_amdgcn_readfirstlane(T.tile_list[slot])
+                                      : T.tile_begin + slot;
     if (T.skip_bad && __builtin_amdgcn_readfirstlane(T.skip_bad[tile / T.tiles_per_chunk])) return;
 
     // rows of this tile, as indices into the buffer's rows
@@ -423,7 +424,7 @@ static void launch_tiles_hint(int hint, dim3 grid, dim3 block, hipStream_t strea
 hipError_t launch_tiles(TileMode mode, const TileTables& t, void* chunks, uint64_t* n_bad,
                         hipStream_t stream)
 {
-    const uint32_t count = t.tile_list ? t.n_list : t.n_tiles;
+    const uint32_t count = (t.tile_list || t.n_list) ? t.n_list : t.n_tiles;
     if (count == 0) return hipSuccess;
     const dim3 grid((count + kWavesPerBlock - 1) / kWavesPerBlock);
     const dim3 block(kWaveSize * kWavesPerBlock);

@@ -24,7 +24,8 @@ struct TileTables {
     uint32_t hint = 3;                        // bit 0: non-temporal tensor-side accesses, bit 1: buffer-side
     // selective restore
     const uint32_t* tile_list = nullptr;      // if set: the n_list tiles to process
-    uint32_t n_list = 0;
+    uint32_t n_list = 0;                      // without a list: > 0 selects tiles [tile_begin, +n_list)
+    uint32_t tile_begin = 0;
     const uint32_t* skip_bad = nullptr;       // if set: bad[] per chunk; tiles of bad chunks are left out
     uint32_t tiles_per_chunk = 1;
 };

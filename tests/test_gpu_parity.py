@@ -381,3 +381,26 @@ def test_full_restore_skip_bad_on_ragged_layout(oracle):
     assert want_n == len(hits) and int(n_bad.item()) == want_n
     assert np.array_equal(_u32(bad), want_bad)
     assert np.array_equal(shard.arena.cpu().numpy(), arena)   # gaps and skipped ranges untouched
+
+
+# ---- snapshot into pinned host memory ----------------------------------------------------------------
+
+@pytest.mark.parametrize("slice_chunks", [1, 5, 1000])
+def test_pack_to_host_equals_pack(oracle, slice_chunks):
+    numels = [int(x) for x in np.random.default_rng(3).integers(1, 90000, size=40)]
+    shard = wl.param_shard("h", numels, 1 << 16, 17, DEV, tiny_recipe=True)
+    plan = ff.plan_for_shard(shard)
+    chunks, crcs, bad, n_bad = ff.alloc_outputs(plan, DEV)
+    chunks.fill_(0xA5)
+    h_chunks = torch.empty(plan.buffer_bytes, dtype=torch.uint8, pin_memory=True).fill_(0x5A)
+    h_crcs = torch.empty(plan.num_chunks, dtype=torch.int32, pin_memory=True).fill_(-1)
+    s_pack, s_copy = torch.cuda.Stream(), torch.cuda.Stream()
+    s_pack.wait_stream(torch.cuda.current_stream())
+    ff.ff_pack_to_host(plan, chunks, crcs, h_chunks, h_crcs, slice_chunks, s_pack, s_copy)
+    s_copy.synchronize()
+    s_pack.synchronize()
+    want_buf, want_crcs = oracle.pack(_host_segments(shard)[0], shard.chunk_bytes, threads=4)
+    assert np.array_equal(h_chunks.numpy(), want_buf)
+    assert np.array_equal(h_crcs.numpy().view(np.uint32), want_crcs)
+    assert np.array_equal(chunks.cpu().numpy(), want_buf)       # the device staging holds it too
+    assert np.array_equal(_u32(crcs), want_crcs)
