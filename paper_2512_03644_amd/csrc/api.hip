@@ -57,11 +57,6 @@ int hip_fail(hipError_t e)
 
 uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
-void fill_constants(TileTables& t)
-{
-    t.x32 = gf2_xpow(32);
-    for (int l = 0; l < 6; l++) t.z[l] = gf2_xpow(128ull << l);
-}
 
 int upload_tables(ff_plan* p)
 {
@@ -71,14 +66,14 @@ int upload_tables(ff_plan* p)
     const uint64_t o_ptr = align_up(o_off + (n + 1) * 8, 256);
     const uint64_t o_first = align_up(o_ptr + n * 8, 256);
     const uint64_t o_tab = align_up(o_first + L.n_tiles * 4, 256);
-    const uint64_t o_partial = align_up(o_tab + 1024 * 4, 256);
+    const uint64_t o_partial = align_up(o_tab + kTabWords * 4, 256);
     std::vector<WorkTile> work;
     if (L.adam_ok && !L.params.empty()) build_work_tiles(L, work);
     if (work.size() > 0xFFFFFFF0ull) return FF_ERR_INVALID;
     const uint64_t o_work = align_up(o_partial + L.n_tiles * 4, 256);
     const uint64_t o_grads = align_up(o_work + work.size() * sizeof(WorkTile), 256);
     const uint64_t o_ftabs = align_up(o_grads + L.params.size() * 8, 256);
-    const uint64_t o_selt = align_up(o_ftabs + 2048 * 4, 256);
+    const uint64_t o_selt = align_up(o_ftabs + kFusedTabWords * 4, 256);
     const uint64_t o_selc = align_up(o_selt + L.n_tiles * 4, 256);
     const uint64_t total = align_up(o_selc + L.n_chunks * 4, 256);
 
@@ -93,8 +88,7 @@ int upload_tables(ff_plan* p)
     std::memcpy(host.data() + o_first, L.tile_first_seg.data(), L.n_tiles * 4);
     build_tab_u(reinterpret_cast<uint32_t*>(host.data() + o_tab));
     if (!work.empty()) std::memcpy(host.data() + o_work, work.data(), work.size() * sizeof(WorkTile));
-    build_tab(reinterpret_cast<uint32_t*>(host.data() + o_ftabs), 1024);
-    build_tab(reinterpret_cast<uint32_t*>(host.data() + o_ftabs) + 1024, 512);
+    build_fused_tabs(reinterpret_cast<uint32_t*>(host.data() + o_ftabs));
 
     FF_HIP_TRY(hipGetDevice(&p->device));
     hipError_t e = hipMalloc(&p->dev_block, total);
@@ -161,7 +155,6 @@ int ff_snapshot_plan(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_byt
     t.lead_rows = 0;
     t.n_tiles = static_cast<uint32_t>(L.n_tiles);
     t.tiles_per_chunk = L.tiles_per_chunk;
-    fill_constants(t);
     // bits 16..18: bit 18 set = take bits 16..17 as the cache-hint selector (tuning knob)
     if (flags & 0x40000u) t.hint = (flags >> 16) & 3u;
     if (L.n_tiles > 0xFFFFFFF0ull) {
@@ -430,7 +423,6 @@ int ff_adam_step_snapshot(const ff_plan* p, const void* const* grads, const ff_a
         if (reinterpret_cast<uint64_t>(grads[i]) % 2) return FF_ERR_INVALID;
     }
     FusedConsts c;
-    fill_fused_crc_consts(c);
     {
         // shared scalars: evaluated in double from the fp32 hyper-parameters, rounded once
         const double lr = hp->lr, b1 = hp->beta1, b2 = hp->beta2, wd = hp->weight_decay;
@@ -470,7 +462,6 @@ int ff_crc32c(const void* dev_buf, uint64_t nbytes, uint32_t* dev_out, void* hip
     const uint32_t tile_rows = 1024;
     if ((rows + tile_rows - 1) / tile_rows > 0xFFFFFFF0ull) return FF_ERR_INVALID;
     TileTables t;
-    fill_constants(t);
     t.total_rows = rows;
     t.tile_rows = tile_rows;
     t.n_tiles = static_cast<uint32_t>((rows + tile_rows - 1) / tile_rows);
@@ -478,18 +469,18 @@ int ff_crc32c(const void* dev_buf, uint64_t nbytes, uint32_t* dev_out, void* hip
     t.payload = rows * 1024;
 
     // scratch: byte tables + one register per tile
-    const uint64_t scratch_bytes = 4096 + (static_cast<uint64_t>(t.n_tiles) + 1) * 4;
+    const uint64_t scratch_bytes = kTabWords * 4 + (static_cast<uint64_t>(t.n_tiles) + 1) * 4;
     void* scratch = nullptr;
     hipError_t e = hipMalloc(&scratch, scratch_bytes);
     if (e == hipErrorOutOfMemory) return FF_ERR_NOMEM;
     FF_HIP_TRY(e);
-    uint32_t tab[1024];
+    uint32_t tab[kTabWords];
     build_tab_u(tab);
     int rc = FF_OK;
     do {
         if ((e = hipMemcpyAsync(scratch, tab, sizeof(tab), hipMemcpyHostToDevice, s)) != hipSuccess) break;
         t.tab_u = static_cast<const uint32_t*>(scratch);
-        t.partial = static_cast<uint32_t*>(scratch) + 1024;
+        t.partial = static_cast<uint32_t*>(scratch) + kTabWords;
         if ((e = launch_tiles(kVerify, t, const_cast<void*>(dev_buf), nullptr, s)) != hipSuccess) break;
         const uint8_t* tail = static_cast<const uint8_t*>(dev_buf) + rows * 1024;
         e = launch_finish_crc(t.partial, t.n_tiles, gf2_xpow(8ull * 1024 * tile_rows), tail,

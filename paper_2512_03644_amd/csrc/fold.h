@@ -130,12 +130,14 @@ __device__ __forceinline__ uint32_t mul_tab(const uint32_t* tab, uint32_t a)
            tab[768 + (a >> 24)];
 }
 
-// State of all lanes -> the CRC register (run from 0) of the rows folded so far, valid in
-// lane 0.  tab: byte tables of x^(8*ROW_BYTES); zl[l] = x^(8 * (ROW_BYTES/64) * 2^l).
+// State of all lanes -> R / x^32, where R is the CRC register (run from 0) of the rows folded so
+// far; the factor x^32 that every register carries is applied once per chunk by the combine
+// step.  The result is valid in every lane.  tab: byte tables of x^(8*ROW_BYTES);
+// lane_c = x^(8 * (ROW_BYTES/64) * (63 - lane)): lane l sits 63 - l lane widths before the end of
+// a row.
 template <class F>
 __device__ __forceinline__ uint32_t reduce_state(const uint32_t (&S)[F::NE][F::NF],
-                                                 const uint32_t* tab, uint32_t x32,
-                                                 const uint32_t (&zl)[6])
+                                                 const uint32_t* tab, uint32_t lane_c)
 {
     constexpr int NE = F::NE, NF = F::NF;
     uint32_t acc[NF];
@@ -145,14 +147,11 @@ __device__ __forceinline__ uint32_t reduce_state(const uint32_t (&S)[F::NE][F::N
         static_for<NF>([&](auto f) { acc[f] = mul_tab(tab, acc[f]) ^ S[e][f]; });
     });
     uint32_t v = acc[NF - 1];
-    static_for<NF - 1>([&](auto i) { v = gf2_mul(v, x32) ^ acc[NF - 2 - i]; });
-    // lane l sits (63 - l) lane widths before the end of the row
+    static_for<NF - 1>([&](auto i) { v = gf2_mul_const<kX32>(v) ^ acc[NF - 2 - i]; });
+    v = gf2_mul(v, lane_c);
 #pragma unroll
-    for (int l = 0; l < 6; l++) {
-        const uint32_t other = __shfl_down(v, 1 << l, kWaveSize);
-        v = gf2_mul(v, zl[l]) ^ other;
-    }
-    return gf2_mul(v, x32);  // the register carries the extra factor x^32
+    for (int l = 0; l < 6; l++) v ^= __shfl_xor(v, 1 << l, kWaveSize);
+    return v;
 }
 
 }  // namespace ffsnap

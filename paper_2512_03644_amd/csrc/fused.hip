@@ -66,13 +66,26 @@ __device__ __forceinline__ void adam_element(const AdamConsts& k, uint32_t g_bit
 struct Lds {
     uint32_t tab16[1024];  // multiply by x^8192  (1 KiB rows)
     uint32_t tab8[1024];   // multiply by x^4096  (512 B rows)
+    uint32_t lane16[64];   // x^(128 * (63 - lane))
+    uint32_t lane8[64];    // x^(64 * (63 - lane))
 };
+
+// Tile registers come out of reduce_state without the factor x^32 that a CRC register carries.
+constexpr uint32_t kX16 = gf2_xpow(16);
 
 __device__ __forceinline__ void add_piece(uint32_t* __restrict__ crcs, const WorkTile& t, int piece,
                                           uint32_t reg)
 {
     if (t.shift[piece])
-        atomicXor(&crcs[t.chunk[piece]], gf2_mul(reg, t.shift[piece]));
+        atomicXor(&crcs[t.chunk[piece]], gf2_mul_const<kX32>(gf2_mul(reg, t.shift[piece])));
+}
+
+// Head piece: the first two bytes of a split element, which are the last two bytes of their
+// chunk.  In the low half of a dword they read M(x) * x^16, and their register is M(x) * x^32.
+__device__ __forceinline__ void add_head_piece(uint32_t* __restrict__ crcs, const WorkTile& t,
+                                               int piece, uint32_t low_half)
+{
+    atomicXor(&crcs[t.chunk[piece]], gf2_mul_const<kX16>(low_half));
 }
 
 // ---- parameter tile ----------------------------------------------------------------------------
@@ -236,7 +249,7 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
                                     const uint32_t d = fx[x - 1][s];
                                     // two message bytes in the low half are M(x) * x^16; their
                                     // register is M(x) * x^32
-                                    add_piece(crcs, t, 3 + x, gf2_mul(d & 0xFFFFu, C.x16));
+                                    add_head_piece(crcs, t, 3 + x, d & 0xFFFFu);
                                     fx[x - 1][s] = d & 0xFFFF0000u;
                                 }
                             }
@@ -257,8 +270,7 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
 // Folding wavefront of stream x (0 = w16, 1..3 = master, m, v).
 template <class F, int DW>
 __device__ __forceinline__ uint32_t fold_stream(const TileGeom& G, Batch (&buf)[2], int x, int lane,
-                                                const uint32_t* tab, uint32_t x32,
-                                                const uint32_t (&zl)[6])
+                                                const uint32_t* tab, uint32_t lane_c)
 {
     constexpr int NE = F::NE;
     static_assert(NE % kBatchRows == 0 && F::NF == DW, "a batch never straddles the rotation");
@@ -286,7 +298,7 @@ __device__ __forceinline__ uint32_t fold_stream(const TileGeom& G, Batch (&buf)[
         }
         __syncthreads();
     }
-    return reduce_state<F>(S, tab, x32, zl);
+    return reduce_state<F>(S, tab, lane_c);
 }
 
 // ---- RAW tile: plain copy into the snapshot -----------------------------------------------------
@@ -332,7 +344,7 @@ __device__ __forceinline__ void run_raw_tile(const WorkTile& t, uint8_t* __restr
             }
         });
     }
-    const uint32_t reg = reduce_state<RawFold>(S, lds.tab16, C.x32, C.z16);
+    const uint32_t reg = reduce_state<RawFold>(S, lds.tab16, lds.lane16[lane]);
     if (lane == 0) add_piece(crcs, t, 0, reg);
 }
 
@@ -346,6 +358,10 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
     for (int i = threadIdx.x; i < 1024; i += blockDim.x) {
         lds.tab16[i] = tabs[i];
         lds.tab8[i] = tabs[1024 + i];
+    }
+    if (threadIdx.x < 64) {
+        lds.lane16[threadIdx.x] = tabs[2048 + threadIdx.x];
+        lds.lane8[threadIdx.x] = tabs[2048 + 64 + threadIdx.x];
     }
     __syncthreads();
     const int lane = threadIdx.x & (kWaveSize - 1);
@@ -375,9 +391,9 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
         const int x = wave - kUpdateWaves;
         uint32_t reg;
         if (x == 0)
-            reg = fold_stream<B16Fold, 2>(G, buf, x, lane, lds.tab8, C.x32, C.z8);
+            reg = fold_stream<B16Fold, 2>(G, buf, x, lane, lds.tab8, lds.lane8[lane]);
         else
-            reg = fold_stream<F32Fold, 4>(G, buf, x, lane, lds.tab16, C.x32, C.z16);
+            reg = fold_stream<F32Fold, 4>(G, buf, x, lane, lds.tab16, lds.lane16[lane]);
         if (lane == 0) add_piece(crcs, t, x, reg);
     }
 }
@@ -403,20 +419,15 @@ __global__ void fused_finish_kernel(uint32_t* __restrict__ crcs, uint64_t n_chun
 
 }  // namespace
 
-void build_tab(uint32_t* tab, uint64_t row_bytes)
+void build_fused_tabs(uint32_t* tab)
 {
-    const uint32_t u = gf2_xpow(8 * row_bytes);
-    for (int k = 0; k < 4; k++)
-        for (uint32_t b = 0; b < 256; b++) tab[k * 256 + b] = gf2_mul(b << (8 * k), u);
-}
-
-void fill_fused_crc_consts(FusedConsts& c)
-{
-    c.x32 = gf2_xpow(32);
-    c.x16 = gf2_xpow(16);
-    for (int l = 0; l < 6; l++) {
-        c.z16[l] = gf2_xpow(128ull << l);
-        c.z8[l] = gf2_xpow(64ull << l);
+    const uint64_t row_bytes[2] = {1024, 512};
+    for (int t = 0; t < 2; t++) {
+        const uint32_t u = gf2_xpow(8 * row_bytes[t]);
+        for (int k = 0; k < 4; k++)
+            for (uint32_t b = 0; b < 256; b++) tab[t * 1024 + k * 256 + b] = gf2_mul(b << (8 * k), u);
+        for (int lane = 0; lane < 64; lane++)
+            tab[2048 + t * 64 + lane] = gf2_xpow(8 * (row_bytes[t] / 64) * (63 - lane));
     }
 }
 

@@ -14,15 +14,13 @@ struct AdamConsts {
 
 struct FusedConsts {
     AdamConsts adam;
-    uint32_t x32, x16;  // x^32, x^16 mod P
-    uint32_t z16[6];    // x^(128 * 2^l): lane merge for 16-byte-per-lane rows
-    uint32_t z8[6];     // x^(64 * 2^l):  lane merge for 8-byte-per-lane rows
 };
 
-void fill_fused_crc_consts(FusedConsts& c);
-
-// tab[4][256]: byte tables of multiplication by x^(8*row_bytes).
-void build_tab(uint32_t* tab, uint64_t row_bytes);
+// Device table of the fused kernels (kFusedTabWords entries): byte tables of multiplication by
+// x^8192 (1 KiB rows) and by x^4096 (512 B rows), then the lane constants x^(128 * (63 - lane))
+// and x^(64 * (63 - lane)).
+constexpr int kFusedTabWords = 2048 + 128;
+void build_fused_tabs(uint32_t* tab);
 
 // Enqueues prepare (crcs = 0, zero tail), the tile kernel and finish (crcs ^= affine).
 // tiles/grads/tabs: device tables (tabs = tables for 1024-byte rows, then for 512-byte rows).

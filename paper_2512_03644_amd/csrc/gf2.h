@@ -9,9 +9,9 @@
 #include <stdint.h>
 
 #if defined(__HIPCC__)
-#define FF_HD __host__ __device__ inline
+#define FF_HD __host__ __device__ constexpr inline
 #else
-#define FF_HD inline
+#define FF_HD constexpr inline
 #endif
 
 namespace ffsnap {
@@ -34,8 +34,25 @@ FF_HD uint32_t gf2_mul(uint32_t a, uint32_t b)
     return p;
 }
 
+// a * C mod P for a multiplier known at compile time: the powers C*x^i fold to literals, which
+// leaves a bit test, an AND and an XOR per bit.
+template <uint32_t C>
+FF_HD uint32_t gf2_mul_const(uint32_t a)
+{
+    uint32_t p = 0, b = C;
+    for (int i = 0; i < 32; i++) {
+        p ^= (a & 0x80000000u) ? b : 0u;
+        a <<= 1;
+        b = gf2_mulx(b);
+    }
+    return p;
+}
+
+// x^32 mod P is the generator without its leading term.
+constexpr uint32_t kX32 = kPolyReflected;
+
 // x^n mod P
-inline uint32_t gf2_xpow(uint64_t n)
+constexpr inline uint32_t gf2_xpow(uint64_t n)
 {
     uint32_t r = kOne, base = kOne >> 1;  // 1, x
     while (n) {

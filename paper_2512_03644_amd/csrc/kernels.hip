@@ -326,7 +326,7 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
         g++;
     }
 
-    const uint32_t reg = reduce_state<Fold>(S, tab, T.x32, T.z);
+    const uint32_t reg = reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]);
     if (lane == 0) partial[tile] = reg;
 }
 
@@ -337,7 +337,7 @@ __device__ __forceinline__ uint32_t chunk_register(const uint32_t* __restrict__ 
 {
     uint32_t acc = 0;
     for (uint32_t i = 0; i < n; i++) acc = gf2_mul(acc, x_tile) ^ partial[first + i];
-    return acc;
+    return gf2_mul_const<kX32>(acc);  // the tiles' registers are stored without their factor x^32
 }
 
 __global__ void combine_pack_kernel(const uint32_t* __restrict__ partial, uint32_t tiles_per_chunk,
@@ -403,6 +403,7 @@ void build_tab_u(uint32_t* tab)
     const uint32_t u = gf2_xpow(8192);
     for (int k = 0; k < 4; k++)
         for (uint32_t b = 0; b < 256; b++) tab[k * 256 + b] = gf2_mul(b << (8 * k), u);
+    for (int lane = 0; lane < 64; lane++) tab[1024 + lane] = gf2_xpow(128ull * (63 - lane));
 }
 
 template <int MODE>

@@ -11,7 +11,8 @@ struct TileTables {
     const uint64_t* seg_off = nullptr;        // [n_seg + 1] stream offsets, seg_off[n_seg] = payload
     const uint64_t* seg_ptr = nullptr;        // [n_seg] device addresses
     const uint32_t* tile_first_seg = nullptr; // [n_tiles]
-    const uint32_t* tab_u = nullptr;          // [4][256] multiply-by-x^8192 byte tables
+    const uint32_t* tab_u = nullptr;          // [4][256] multiply-by-x^8192 byte tables, then
+                                              // [64] lane constants x^(128 * (63 - lane))
     uint32_t* partial = nullptr;              // [n_tiles] register of every tile run from 0
     uint64_t payload = 0;                     // N
     uint64_t total_rows = 0;                  // 1 KiB rows in the buffer
@@ -19,8 +20,6 @@ struct TileTables {
     uint32_t tile_rows = 0;                   // rows per tile
     uint32_t lead_rows = 0;                   // rows missing at the front of tile 0
     uint32_t n_tiles = 0;
-    uint32_t x32 = 0;                         // x^32 mod P
-    uint32_t z[6] = {0, 0, 0, 0, 0, 0};       // x^(128 * 2^l) mod P
     uint32_t hint = 3;                        // bit 0: non-temporal tensor-side accesses, bit 1: buffer-side
     // selective restore
     const uint32_t* tile_list = nullptr;      // if set: the n_list tiles to process
@@ -60,7 +59,9 @@ hipError_t launch_zero_u64(uint64_t* p, hipStream_t stream);
 
 hipError_t launch_copy(void* dst, const void* src, uint64_t nbytes, hipStream_t stream);
 
-// Fills tab[4][256] (host) with the byte tables of multiplication by x^8192.
+// Fills tab (host, kTabWords entries): byte tables of multiplication by x^8192, then the 64 lane
+// constants x^(128 * (63 - lane)).
+constexpr int kTabWords = 1024 + 64;
 void build_tab_u(uint32_t* tab);
 
 }  // namespace ffsnap

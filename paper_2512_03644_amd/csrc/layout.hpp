@@ -55,7 +55,7 @@ struct WorkTile {
 };
 
 constexpr uint32_t kWorkParam = 0, kWorkRaw = 1;
-constexpr uint32_t kParamTileElems = 1u << 16;
+constexpr uint32_t kParamTileElems = 1u << 14;
 constexpr uint32_t kRawTileBytes = 1u << 18;
 
 // Work list of the fused step over the whole layout (needs L.adam_ok).
@@ -67,6 +67,6 @@ void build_work_tiles(const Layout& L, std::vector<WorkTile>& out);
 int build_layout(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_bytes, unsigned tile_log2,
                  Layout& out);
 
-constexpr uint64_t kDefaultTileBytes = 1ull << 18;
+constexpr uint64_t kDefaultTileBytes = 1ull << 15;
 
 }  // namespace ffsnap
