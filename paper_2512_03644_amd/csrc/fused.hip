@@ -1,6 +1,6 @@
 // Fused optimizer step + snapshot for gfx950.
 //
-// A workgroup owns one work tile (layout.hpp): a run of up to 65536 elements of one parameter
+// A workgroup owns one work tile (layout.hpp): a run of up to kParamTileElems elements of one parameter
 // group, or a run of bytes of a RAW segment.  A parameter tile is walked in rows of 256
 // elements, lane l taking 4 consecutive elements: 8 bytes of bf16 gradient and 3 x 16 bytes of
 // fp32 master/m/v come in, the AdamW update runs in registers, and the four results go out
@@ -270,7 +270,7 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
 // Folding wavefront of stream x (0 = w16, 1..3 = master, m, v).
 template <class F, int DW>
 __device__ __forceinline__ uint32_t fold_stream(const TileGeom& G, Batch (&buf)[2], int x, int lane,
-                                                const uint32_t* tab, uint32_t lane_c)
+                                                const uint32_t* tab, const uint32_t* lane_tab)
 {
     constexpr int NE = F::NE;
     static_assert(NE % kBatchRows == 0 && F::NF == DW, "a batch never straddles the rotation");
@@ -298,7 +298,7 @@ __device__ __forceinline__ uint32_t fold_stream(const TileGeom& G, Batch (&buf)[
         }
         __syncthreads();
     }
-    return reduce_state<F>(S, tab, lane_c);
+    return reduce_state<F>(S, tab, lane_tab[lane]);  // tables are complete after any barrier
 }
 
 // ---- RAW tile: plain copy into the snapshot -----------------------------------------------------
@@ -355,30 +355,29 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
 {
     __shared__ Lds lds;
     __shared__ Batch buf[2];
-    for (int i = threadIdx.x; i < 1024; i += blockDim.x) {
-        lds.tab16[i] = tabs[i];
-        lds.tab8[i] = tabs[1024 + i];
-    }
-    if (threadIdx.x < 64) {
-        lds.lane16[threadIdx.x] = tabs[2048 + threadIdx.x];
-        lds.lane8[threadIdx.x] = tabs[2048 + 64 + threadIdx.x];
-    }
-    __syncthreads();
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
     const uint32_t ti = blockIdx.x;  // one tile per workgroup
     if (ti >= n_tiles) return;
-    // the tile descriptor is uniform: read it through scalar registers
-    WorkTile t;
-    {
-        const uint32_t* src = reinterpret_cast<const uint32_t*>(tiles + ti);
-        uint32_t* dst = reinterpret_cast<uint32_t*>(&t);
-#pragma unroll
-        for (unsigned i = 0; i < sizeof(WorkTile) / 4; i++)
-            dst[i] = __builtin_amdgcn_readfirstlane(src[i]);
+    // The reduction tables are used after the last barrier of a tile only (every tile passes at
+    // least two), so the folding wavefronts fetch them while the updating wavefronts are already
+    // loading their first rows.
+    if (wave >= kUpdateWaves) {
+        for (int i = threadIdx.x - kUpdateWaves * kWaveSize; i < 1024; i += kFoldWaves * kWaveSize) {
+            lds.tab16[i] = tabs[i];
+            lds.tab8[i] = tabs[1024 + i];
+        }
+        if (wave == kUpdateWaves) {
+            lds.lane16[lane] = tabs[2048 + lane];
+            lds.lane8[lane] = tabs[2048 + 64 + lane];
+        }
     }
+    // the tile descriptor is uniform and read-only: the loads below go through scalar registers
+    // (a private copy indexed by the stream number would live in scratch memory instead)
+    const WorkTile& t = tiles[ti];
     if (t.kind != kWorkParam) {
-        // RAW bytes: one wavefront copies and folds; no barrier follows, the others just leave
+        // RAW bytes: one wavefront copies and folds, the others just leave
+        __syncthreads();  // tables complete
         if (wave == 0) run_raw_tile(t, chunks, crcs, C, lds, lane);
         return;
     }
@@ -391,9 +390,9 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
         const int x = wave - kUpdateWaves;
         uint32_t reg;
         if (x == 0)
-            reg = fold_stream<B16Fold, 2>(G, buf, x, lane, lds.tab8, lds.lane8[lane]);
+            reg = fold_stream<B16Fold, 2>(G, buf, x, lane, lds.tab8, lds.lane8);
         else
-            reg = fold_stream<F32Fold, 4>(G, buf, x, lane, lds.tab16, lds.lane16[lane]);
+            reg = fold_stream<F32Fold, 4>(G, buf, x, lane, lds.tab16, lds.lane16);
         if (lane == 0) add_piece(crcs, t, x, reg);
     }
 }

@@ -55,7 +55,7 @@ struct WorkTile {
 };
 
 constexpr uint32_t kWorkParam = 0, kWorkRaw = 1;
-constexpr uint32_t kParamTileElems = 1u << 14;
+constexpr uint32_t kParamTileElems = 1u << 13;
 constexpr uint32_t kRawTileBytes = 1u << 18;
 
 // Work list of the fused step over the whole layout (needs L.adam_ok).

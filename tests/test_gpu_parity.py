@@ -230,7 +230,7 @@ def _adam_and_compare(oracle, numels, chunk, seed, hp=HP, extra_raw=None):
 @pytest.mark.parametrize("chunk", [1024, 4096, 1 << 16, 1 << 20])
 def test_fused_adam_small_ragged(oracle, chunk):
     # odd element counts put fp32 segments at stream offsets 2 mod 4, so elements straddle
-    # chunk boundaries; counts below and above one 256-element row and one 65536-element tile
+    # chunk boundaries; counts below and above one 256-element row and several tiles
     numels = [1, 3, 255, 256, 257, 1000, 4097, 70001, 131072, 65536 + 255, 5, 77]
     _adam_and_compare(oracle, numels, chunk, seed=chunk)
 
