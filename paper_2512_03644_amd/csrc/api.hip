@@ -23,6 +23,10 @@ struct ff_plan {
     void* dev_block = nullptr;  // one allocation holding every device table
     TileTables tables;
     uint32_t x_tile = 0;  // x^(8 * tile_bytes)
+    // A pass that only reads (verify) runs fastest on larger tiles than one that also writes:
+    // it folds verify_group consecutive tiles as one.
+    uint32_t verify_group = 1;
+    uint32_t x_verify_tile = 0;  // x^(8 * tile_bytes * verify_group)
     uint32_t affine = 0;  // preset/complement term of a chunk_bytes-long CRC
     // fused optimizer step (only when every parameter group is complete)
     const WorkTile* work = nullptr;
@@ -147,6 +151,10 @@ int ff_snapshot_plan(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_byt
     p->host_only = (flags & FF_PLAN_HOST_ONLY) != 0;
     p->x_tile = gf2_xpow(8 * L.tile_bytes);
     p->affine = crc_affine_term(L.chunk_bytes);
+    while (L.tile_bytes * p->verify_group < kVerifyTileBytes &&
+           p->verify_group * 2 <= L.tiles_per_chunk)
+        p->verify_group *= 2;  // tiles_per_chunk is a power of two
+    p->x_verify_tile = gf2_xpow(8 * L.tile_bytes * p->verify_group);
     TileTables& t = p->tables;
     t.payload = L.payload;
     t.total_rows = L.buffer_bytes / 1024;
@@ -266,10 +274,19 @@ int restore_impl(const ff_plan* p, const void* chunks, const uint32_t* crcs, uin
     const bool verify_only = (flags & FF_RESTORE_VERIFY_ONLY) != 0;
     const bool skip_bad = (flags & FF_RESTORE_SKIP_BAD) != 0;
     if (verify_only || skip_bad) {
-        // pass 1: read and fold only
-        FF_HIP_TRY(launch_tiles(kVerify, t, buf, n_bad, s));
-        FF_HIP_TRY(launch_combine_verify(t.partial, L.tiles_per_chunk, p->x_tile, p->affine,
-                                         n_verify, chunk_list, crcs, bad, n_bad, s));
+        // pass 1: read and fold only; over the whole buffer it runs on grouped tiles
+        TileTables v = t;
+        uint32_t tpc = L.tiles_per_chunk, x_tile = p->x_tile;
+        if (!selected) {
+            v.tile_rows *= p->verify_group;
+            v.n_tiles /= p->verify_group;
+            tpc /= p->verify_group;
+            v.tiles_per_chunk = tpc;
+            x_tile = p->x_verify_tile;
+        }
+        FF_HIP_TRY(launch_tiles(kVerify, v, buf, n_bad, s));
+        FF_HIP_TRY(launch_combine_verify(v.partial, tpc, x_tile, p->affine, n_verify, chunk_list,
+                                         crcs, bad, n_bad, s));
         if (verify_only) return FF_OK;
         // pass 2: scatter the tiles of the chunks that verified
         t.skip_bad = bad;

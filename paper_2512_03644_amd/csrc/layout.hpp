@@ -67,6 +67,9 @@ void build_work_tiles(const Layout& L, std::vector<WorkTile>& out);
 int build_layout(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_bytes, unsigned tile_log2,
                  Layout& out);
 
+// 32 KiB tiles keep the region the chip is sweeping at any moment compact, which is what a pass
+// that reads and writes needs; a read-only pass amortises the per-tile reduction better on 64 KiB.
 constexpr uint64_t kDefaultTileBytes = 1ull << 15;
+constexpr uint64_t kVerifyTileBytes = 1ull << 16;
 
 }  // namespace ffsnap

@@ -143,6 +143,57 @@ def test_corruption_is_flagged_exactly(oracle):
     assert all(bool((t.view(torch.uint8) == 0xA5).all()) for t in shard.segments)
 
 
+@pytest.mark.parametrize("chunk,tile_log2", [(1 << 15, 0), (1 << 16, 0), (1 << 16, 12), (1 << 18, 0),
+                                             (1 << 20, 14), (1 << 17, 17)])
+def test_verify_only_every_tile_position(oracle, chunk, tile_log2):
+    """A read-only pass folds several tiles as one; a flipped bit in any tile of a chunk, and at
+    the first and last byte of a chunk, must flag exactly that chunk."""
+    numels = [int(x) for x in np.random.default_rng(chunk + tile_log2).integers(20000, 200000, size=12)]
+    shard = wl.param_shard("v", numels, chunk, 31, DEV, tiny_recipe=True)
+    plan, chunks, crcs, bad, n_bad, want_buf, want_crcs = _pack_and_compare(shard, oracle, tile_log2)
+    tile = 1 << (tile_log2 or 15)
+    tile = min(tile, chunk)
+    rng = np.random.default_rng(7)
+    dirty = chunks.clone()
+    hit = []
+    for c in range(plan.num_chunks):
+        k = c % (chunk // tile + 2)           # tile position inside the chunk; two extra cases
+        if k == chunk // tile:
+            off = 0
+        elif k == chunk // tile + 1:
+            off = chunk - 1
+        else:
+            off = k * tile + int(rng.integers(0, tile))
+        if c % 3 != 2:                        # leave every third chunk clean
+            dirty[c * chunk + off] ^= (1 << int(rng.integers(0, 8)))
+            hit.append(c)
+    _poison_segments(shard)
+    ff.ff_restore(plan, dirty, crcs, bad, n_bad, flags=ff.FF_RESTORE_VERIFY_ONLY)
+    torch.cuda.synchronize()
+    want_bad, want_n = oracle.verify(dirty.cpu().numpy(), want_crcs, chunk)
+    assert want_n == len(hit) and list(np.nonzero(want_bad)[0]) == hit
+    assert int(n_bad.item()) == want_n
+    assert np.array_equal(_u32(bad), want_bad)
+    assert all(bool((t.view(torch.uint8) == 0xA5).all()) for t in shard.segments)
+    # clean buffer: nothing flagged
+    ff.ff_restore(plan, chunks, crcs, bad, n_bad, flags=ff.FF_RESTORE_VERIFY_ONLY)
+    torch.cuda.synchronize()
+    assert int(n_bad.item()) == 0 and int(bad.sum().item()) == 0
+    # skip-bad: chunks that verify are scattered, the others leave their ranges untouched
+    _poison_segments(shard)
+    ff.ff_restore(plan, dirty, crcs, bad, n_bad, flags=ff.FF_RESTORE_SKIP_BAD)
+    torch.cuda.synchronize()
+    assert np.array_equal(_u32(bad), want_bad)
+    got = np.concatenate(_host_segments(shard)[0])
+    clean = chunks.cpu().numpy()[:got.size]
+    for c in range(plan.num_chunks):
+        lo, hi = c * chunk, min((c + 1) * chunk, got.size)
+        if want_bad[c]:
+            assert bool((got[lo:hi] == 0xA5).all())
+        else:
+            assert np.array_equal(got[lo:hi], clean[lo:hi])
+
+
 def test_device_call_argument_errors():
     a = torch.zeros(4096, dtype=torch.float32, device=DEV)
     plan = ff.ff_snapshot_plan([a], 4096)
