@@ -77,6 +77,13 @@ typedef struct {
 #define FF_PLAN_HOST_ONLY 1u /* build the layout only: no device memory is touched, queries work,
                                 device calls return FF_ERR_HOST_ONLY (lets a sender or a test
                                 compute sizes and the layout id without a GPU)                  */
+/* Tuning fields of the plan flags; 0 selects the defaults, results never depend on them.
+ *   bits 8..15   log2 of the tile size in bytes (the stream range one wavefront folds; clamped to
+ *                [10, log2(chunk_bytes)]; default 15)
+ *   bits 16..18  bit 18 set: bits 16..17 choose non-temporal accesses on the tensor side (bit 16)
+ *                and on the chunk-buffer side (bit 17); default both                             */
+#define FF_PLAN_TILE_LOG2(n) (((uint32_t)(n) & 0xFFu) << 8)
+#define FF_PLAN_CACHE_HINT(h) (0x40000u | (((uint32_t)(h) & 3u) << 16))
 
 /* ff_restore flags */
 #define FF_RESTORE_VERIFY_ONLY 1u /* recompute and compare CRCs, write bad[]/n_bad, scatter nothing */
