@@ -32,6 +32,12 @@ constexpr int kRowBytes = Fold::ROW_BYTES;
 constexpr int kNE = Fold::NE;
 constexpr int kNF = Fold::NF;
 constexpr int kDepth = 8;  // rows in flight per wavefront
+// A default-size tile that lies inside one segment is processed by straight-line code with a
+// deeper queue: with no loop there is no loop-carried register to copy and no wait for all
+// outstanding loads at a loop head.
+constexpr int kWholeRows = 32;   // rows of a default (32 KiB) tile
+constexpr int kWholeDepth = 16;  // rows in flight on that path
+static_assert(kWholeRows % kNE == 0 && kWholeDepth <= kWholeRows, "whole-tile path");
 static_assert(kNE % kDepth == 0, "queue slots must repeat with the state rotation");
 static_assert(kNF == 4 && kRowBytes == 1024, "one 16-byte word per lane per row");
 
@@ -237,6 +243,40 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
 
     uint32_t S[kNE][kNF];
     static_for<kNE>([&](auto e) { static_for<kNF>([&](auto f) { S[e][f] = 0; }); });
+
+    // Whole-tile path: all rows real, and on the tensor side inside one segment.
+    if (T.tile_rows == kWholeRows && R == kWholeRows) {
+        const uint8_t* bp = chunks + s_base + lane16;  // buffer side
+        const uint8_t* tp = bp;                        // tensor side
+        bool whole = true;
+        if (MODE == kPack) whole = span_in_segment(cin, s_base, kWholeRows, &tp);
+        if (MODE == kRestore) whole = span_in_segment(cout, s_base, kWholeRows, &tp);
+        if (whole) {
+            auto fetch = [&](int r) {
+                return (MODE == kPack) ? load16_unaligned<kSegNT>(tp + r * kRowBytes)
+                                       : load16_stream<kBufNT>(bp + r * kRowBytes);
+            };
+            u32x4 w[kWholeDepth];
+            static_for<kWholeDepth>([&](auto k) { w[k] = fetch(k); });
+            static_for<kWholeRows>([&](auto Jc) {
+                constexpr int J = Jc;
+                const u32x4 x = w[J % kWholeDepth];
+                if (MODE == kPack)
+                    store16_stream<kBufNT>(const_cast<uint8_t*>(bp) + J * kRowBytes, x);
+                if (MODE == kRestore)
+                    store16_unaligned<kSegNT>(const_cast<uint8_t*>(tp) + J * kRowBytes, x);
+                fold_word<J % kNE>(S, x);
+                if constexpr (J + kWholeDepth < kWholeRows) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    w[J % kWholeDepth] = fetch(J + kWholeDepth);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            });
+            const uint32_t reg = reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]);
+            if (lane == 0) partial[tile] = reg;
+            return;
+        }
+    }
 
     // queue slot of row r is (r + pad) mod kDepth; fill the first kDepth rows
     u32x4 q[kDepth];
