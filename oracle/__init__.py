@@ -68,6 +68,13 @@ def lib():
         L.orc_f32_to_bf16.argtypes = [ctypes.c_float]
         L.orc_adam_f32.restype = None
         L.orc_adam_f32.argtypes = [u64] + [ctypes.c_void_p] * 5 + [ctypes.POINTER(AdamHParams)]
+        L.orc_f16_to_f32_array.restype = None
+        L.orc_f16_to_f32_array.argtypes = [u64, ctypes.c_void_p, ctypes.c_void_p]
+        L.orc_f32_to_f16_array.restype = None
+        L.orc_f32_to_f16_array.argtypes = [u64, ctypes.c_void_p, ctypes.c_void_p]
+        L.orc_adam_f32_f16.restype = None
+        L.orc_adam_f32_f16.argtypes = ([u64, ctypes.c_void_p, ctypes.c_float] + [ctypes.c_void_p] * 4 +
+                                       [ctypes.POINTER(AdamHParams), u64p])
         L.orc_adam_f64.restype = None
         L.orc_adam_f64.argtypes = ([u64] + [ctypes.c_void_p] * 4 + [ctypes.c_double] * 5 + [u32])
         L.orc_init()
@@ -230,6 +237,37 @@ def adam_f32(grad_bf16, master, m, v, w16, lr, beta1, beta2, eps, weight_decay, 
                        v.ctypes.data, w16.ctypes.data, ctypes.byref(h))
 
 
+def f16_to_f32(bits):
+    """fp16 bit patterns (uint16 array) -> float32 array."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    out = np.empty(bits.shape, dtype=np.float32)
+    lib().orc_f16_to_f32_array(bits.size, bits.ctypes.data, out.ctypes.data)
+    return out
+
+
+def f32_to_f16(x):
+    """float32 array -> fp16 bit patterns (uint16 array), round to nearest even."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint16)
+    lib().orc_f32_to_f16_array(x.size, x.ctypes.data, out.ctypes.data)
+    return out
+
+
+def adam_f32_f16(grad_f16, inv_scale, master, m, v, w16, lr, beta1, beta2, eps, weight_decay, step):
+    """In-place fp32 AdamW step for fp16 training with a loss scale.  grad_f16, w16: uint16 arrays
+    holding fp16 bit patterns.  Returns the number of non-finite gradient elements."""
+    n = master.size
+    for a, dt in ((grad_f16, np.uint16), (w16, np.uint16), (master, np.float32),
+                  (m, np.float32), (v, np.float32)):
+        assert a.dtype == dt and a.size == n and a.flags["C_CONTIGUOUS"]
+    h = AdamHParams(lr, beta1, beta2, eps, weight_decay, step)
+    bad = ctypes.c_uint64(0)
+    lib().orc_adam_f32_f16(n, grad_f16.ctypes.data, ctypes.c_float(inv_scale), master.ctypes.data,
+                           m.ctypes.data, v.ctypes.data, w16.ctypes.data, ctypes.byref(h),
+                           ctypes.byref(bad))
+    return int(bad.value)
+
+
 def adam_f64(grad, master, m, v, lr, beta1, beta2, eps, weight_decay, step):
     n = master.size
     for a in (grad, master, m, v):
@@ -245,6 +283,15 @@ def adam_snapshot(params, grads_bf16, segments, chunk_bytes, hparams, threads=1)
     for (w16, master, m, v), g in zip(params, grads_bf16):
         adam_f32(g, master, m, v, w16, **hparams)
     return pack(segments, chunk_bytes, threads=threads)
+
+
+def adam_snapshot_f16(params, grads_f16, inv_scale, segments, chunk_bytes, hparams, threads=1):
+    """The fp16 variant of adam_snapshot.  Returns (buffer, crcs, n_nonfinite)."""
+    bad = 0
+    for (w16, master, m, v), g in zip(params, grads_f16):
+        bad += adam_f32_f16(g, inv_scale, master, m, v, w16, **hparams)
+    buf, crcs = pack(segments, chunk_bytes, threads=threads)
+    return buf, crcs, bad
 
 
 def razor_unique(kinds, dp_degree, distributed_optimizer):

@@ -302,6 +302,104 @@ void orc_adam_f32(uint64_t n, const uint16_t *grad, float *master, float *m, flo
     }
 }
 
+/* ---- fp16 variant (the paper trains in fp16, section 7.1) ------------------------------------
+ * IEEE 754 binary16 decoded by its definition: (-1)^s * 2^(e-15) * (1 + f/1024), subnormals
+ * 2^-14 * f/1024; infinities and NaNs keep sign and payload (payload moved to the top bits). */
+float orc_f16_to_f32(uint16_t h)
+{
+    int e = (h >> 10) & 0x1F;
+    uint32_t f = h & 0x3FFu;
+    float r;
+    if (e == 31) {
+        uint32_t u = 0x7F800000u | (f << 13);
+        memcpy(&r, &u, 4);
+    } else if (e == 0) {
+        r = (float)ldexp((double)f, -24);
+    } else {
+        r = (float)ldexp((double)(f + 1024u), e - 25);
+    }
+    return (h & 0x8000u) ? -r : r;
+}
+
+/* binary32 -> binary16, round to nearest even by the definition: the representable neighbours
+ * of |x| are multiples of the quantum 2^(max(E, -14) - 10), E = floor(log2 |x|); the nearest
+ * multiple is taken (ties to the even one) and anything that rounds to 2^16 or more is
+ * infinity.  NaN keeps sign and the top 9 payload bits and is forced quiet. */
+uint16_t orc_f32_to_f16(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u)
+        return (uint16_t)(sign | 0x7E00u | ((u >> 13) & 0x1FFu));
+    double a = fabs((double)x);
+    if (a == 0.0) return sign;
+    if (isinf(a)) return (uint16_t)(sign | 0x7C00u);
+    int ex;
+    (void)frexp(a, &ex); /* a = frac * 2^ex, frac in [0.5, 1): E = ex - 1 */
+    int E = ex - 1;
+    if (E < -14) E = -14;
+    double quantum = ldexp(1.0, E - 10);
+    double q = nearbyint(a / quantum); /* default rounding mode: to nearest, ties to even */
+    double r = q * quantum;
+    if (r >= 65536.0) return (uint16_t)(sign | 0x7C00u);
+    if (r == 0.0) return sign;
+    /* encode r, which is exactly representable */
+    (void)frexp(r, &ex);
+    E = ex - 1;
+    if (E < -14) return (uint16_t)(sign | (uint16_t)ldexp(r, 24)); /* subnormal: f = r * 2^24 */
+    uint32_t f = (uint32_t)ldexp(r, 10 - E) - 1024u;
+    return (uint16_t)(sign | ((uint32_t)(E + 15) << 10) | f);
+}
+
+/* Element-wise conversions of arrays (for tests that sweep every fp16 value). */
+void orc_f16_to_f32_array(uint64_t n, const uint16_t *in, float *out)
+{
+    for (uint64_t i = 0; i < n; i++) out[i] = orc_f16_to_f32(in[i]);
+}
+
+void orc_f32_to_f16_array(uint64_t n, const float *in, uint16_t *out)
+{
+    for (uint64_t i = 0; i < n; i++) out[i] = orc_f32_to_f16(in[i]);
+}
+
+/* The Adam step of orc_adam_f32 for fp16 training with a loss scale: the gradient is fp16 and
+ * was computed on a loss multiplied by S, so g = float(grad) * inv_scale (inv_scale = 1/S, one
+ * rounded fp32 multiplication); the working weights are the fp16 rounding of the new master.
+ * *n_nonfinite gets the number of gradient elements that are infinite or NaN (the caller's
+ * signal to lower S and to fall back to the previous snapshot); the update itself is applied
+ * to every element by the same arithmetic. */
+void orc_adam_f32_f16(uint64_t n, const uint16_t *grad, float inv_scale, float *master, float *m,
+                      float *v, uint16_t *w16, const orc_adam_hparams *h, uint64_t *n_nonfinite)
+{
+    adam_consts k = derive_consts(h);
+    uint64_t bad = 0;
+    for (uint64_t i = 0; i < n; i++) {
+        volatile float g_raw = orc_f16_to_f32(grad[i]);
+        if (isinf(g_raw) || isnan(g_raw)) bad++;
+        volatile float g = g_raw * inv_scale;
+        volatile float p = master[i] * k.decay;
+        volatile float m_a = k.b1 * m[i];
+        volatile float m_b = k.omb1 * g;
+        volatile float m1 = m_a + m_b;
+        volatile float v_a = k.b2 * v[i];
+        volatile float v_b = k.omb2 * g;
+        volatile float v_c = v_b * g;
+        volatile float v1 = v_a + v_c;
+        volatile float r = sqrtf(v1);
+        volatile float d0 = r / k.bc2s;
+        volatile float d = d0 + k.eps;
+        volatile float q = m1 / d;
+        volatile float u = k.step_size * q;
+        volatile float p1 = p - u;
+        master[i] = p1;
+        m[i] = m1;
+        v[i] = v1;
+        w16[i] = orc_f32_to_f16(p1);
+    }
+    if (n_nonfinite) *n_nonfinite = bad;
+}
+
 /* The same step with every quantity in double: the sanity reference for small tensors. */
 void orc_adam_f64(uint64_t n, const double *grad, double *master, double *m, double *v,
                   double lr, double beta1, double beta2, double eps, double weight_decay,

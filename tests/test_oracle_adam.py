@@ -134,3 +134,145 @@ def test_bf16_rounding_cases(oracle):
     for u in (0x7F800001, 0x7FC00000, 0xFF800001, 0x7FFFFFFF, 0x7F80FFFF):
         h = oracle.lib().orc_f32_to_bf16(np.array([u], dtype=np.uint32).view(np.float32)[0])
         assert (h & 0x7F80) == 0x7F80 and (h & 0x007F) != 0 and (h >> 15) == (u >> 31)
+
+
+# ---- fp16 variant: conversions and the loss-scaled step ------------------------------------------
+
+def test_f16_decode_every_value(oracle):
+    bits = np.arange(65536, dtype=np.uint16)
+    got = oracle.f16_to_f32(bits)
+    want = bits.view(np.float16).astype(np.float32)        # numpy's IEEE conversion, exact
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got.view(np.uint32)[~nan], want.view(np.uint32)[~nan])
+    # closed form of a few values
+    for h, x in [(0x3C00, 1.0), (0xC000, -2.0), (0x7BFF, 65504.0), (0x0001, 2.0 ** -24),
+                 (0x0400, 2.0 ** -14), (0x03FF, 1023 * 2.0 ** -24), (0x8000, -0.0)]:
+        r = oracle.f16_to_f32(np.array([h], dtype=np.uint16))[0]
+        assert r == np.float32(x) and np.signbit(r) == np.signbit(np.float32(x))
+    assert np.isposinf(oracle.f16_to_f32(np.array([0x7C00], dtype=np.uint16))[0])
+
+
+def test_f16_encode_round_trip_ties_and_limits(oracle):
+    bits = np.arange(65536, dtype=np.uint16)
+    vals = bits.view(np.float16).astype(np.float32)
+    finite = ~np.isnan(vals)
+    # every fp16 value survives the round trip
+    assert np.array_equal(oracle.f32_to_f16(vals[finite]), bits[finite])
+    # every midpoint between neighbouring positive fp16 values (exact in fp32) goes to the even one
+    lo = np.arange(0, 0x7BFF, dtype=np.uint16)
+    a = lo.view(np.float16).astype(np.float64)
+    b = (lo + 1).astype(np.uint16).view(np.float16).astype(np.float64)
+    mid = ((a + b) / 2).astype(np.float32)
+    assert np.array_equal(mid.astype(np.float64), (a + b) / 2)
+    want = np.where(lo % 2 == 0, lo, lo + 1).astype(np.uint16)
+    assert np.array_equal(oracle.f32_to_f16(mid), want)
+    assert np.array_equal(oracle.f32_to_f16(-mid), want | 0x8000)
+    # one fp32 step to either side of a midpoint goes to the nearer neighbour
+    up = np.nextafter(mid, np.float32(np.inf))
+    dn = np.nextafter(mid, np.float32(-np.inf))
+    assert np.array_equal(oracle.f32_to_f16(up), lo + 1)
+    assert np.array_equal(oracle.f32_to_f16(dn[1:]), lo[1:])
+    # limits: the largest value, the overflow threshold 65520, underflow to zero at 2^-25
+    one = lambda x: int(oracle.f32_to_f16(np.array([x], dtype=np.float32))[0])
+    assert one(65504.0) == 0x7BFF and one(np.nextafter(np.float32(65520), np.float32(0))) == 0x7BFF
+    assert one(65520.0) == 0x7C00 and one(1e9) == 0x7C00 and one(-1e9) == 0xFC00
+    assert one(np.inf) == 0x7C00 and one(-np.inf) == 0xFC00
+    assert one(2.0 ** -25) == 0 and one(np.nextafter(np.float32(2.0 ** -25), np.float32(1))) == 1
+    assert one(-(2.0 ** -25)) == 0x8000 and one(0.0) == 0 and one(-0.0) == 0x8000
+    assert one(1e-30) == 0 and one(2.0 ** -24) == 1 and one(2.0 ** -14) == 0x0400
+    # NaN: quiet, sign and top payload bits kept
+    q = np.array([0x7FC00000, 0xFFC00000, 0x7F800001, 0x7FA12345], dtype=np.uint32).view(np.float32)
+    got = oracle.f32_to_f16(q)
+    assert list(got) == [0x7E00, 0xFE00, 0x7E00, 0x7E00 | (0x212345 >> 13)]
+
+
+def test_f16_encode_matches_numpy_on_random_values(oracle):
+    rng = np.random.default_rng(99)
+    x = np.concatenate([rng.normal(0, 1, 200000), rng.normal(0, 1e-5, 100000),
+                        rng.normal(0, 3e4, 100000),
+                        np.exp(rng.uniform(-20, 12, 200000)) * rng.choice([-1, 1], 200000)])
+    x = x.astype(np.float32)
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).view(np.uint16)          # library routine: IEEE RNE
+    assert np.array_equal(oracle.f32_to_f16(x), want)
+
+
+def _draw_f16(n, seed, scale):
+    rng = np.random.default_rng(seed)
+    master = rng.normal(0, 0.02, n).astype(np.float32)
+    m = rng.normal(0, 1e-3, n).astype(np.float32)
+    v = (rng.normal(0, 1e-3, n).astype(np.float32)) ** 2
+    g = (rng.normal(0, 1e-3, n) * scale).astype(np.float16)  # gradient of the scaled loss
+    return master, m, v, g.view(np.uint16).copy()
+
+
+@pytest.mark.parametrize("step,scale", [(1, 1.0), (7, 1024.0), (1000, 65536.0)])
+def test_f16_step_close_to_f64_step(oracle, step, scale):
+    hp = dict(HP, step=step)
+    n = 4096
+    master, m, v, gb = _draw_f16(n, 41 + step, scale)
+    inv = float(np.float32(1.0 / scale))
+    g64 = gb.view(np.float16).astype(np.float64) * inv
+    M, A, B = (x.astype(np.float64) for x in (master, m, v))
+    hp64 = {k: (_f32(x) if k != "step" else x) for k, x in hp.items()}
+    oracle.adam_f64(g64.copy(), M, A, B, **hp64)
+    w16 = np.zeros(n, dtype=np.uint16)
+    p, a, b = master.copy(), m.copy(), v.copy()
+    bad = oracle.adam_f32_f16(gb, inv, p, a, b, w16, **hp)
+    assert bad == 0
+    u = 2.0 ** -24
+    # same cancellation-aware bounds as for the bf16 step; the unscaling adds one rounding of g
+    bound_m = 6 * u * (np.abs(0.9 * m.astype(np.float64)) + np.abs(0.1 * g64)) + 1e-45
+    assert np.all(np.abs(a - A) <= bound_m)
+    np.testing.assert_allclose(b, B, rtol=12 * u, atol=1e-45)
+    d = np.sqrt(B) / np.sqrt(1 - hp64["beta2"] ** step) + hp64["eps"]
+    ss = hp64["lr"] / (1 - hp64["beta1"] ** step)
+    bound_p = 8 * u * (np.abs(master) + ss * np.abs(A) / d) + ss * bound_m / d
+    assert np.all(np.abs(p - M) <= bound_p)
+    # the fp16 weights are the rounding of the new master (checked with numpy's conversion)
+    assert np.array_equal(w16, p.astype(np.float16).view(np.uint16))
+
+
+def test_f16_step_equals_bf16_step_on_shared_values(oracle):
+    """Gradients that both 16-bit formats represent exactly (small powers of two times small
+    integers) with a loss scale of one: master, m and v must come out bit-identical to the bf16
+    step's, whose arithmetic is pinned above."""
+    rng = np.random.default_rng(5)
+    n = 2048
+    master, m, v, _ = _draw_f16(n, 77, 1.0)
+    g = (rng.integers(-7, 8, n) * 2.0 ** rng.integers(-12, -4, n)).astype(np.float32)
+    g_f16 = g.astype(np.float16)
+    g_bf16 = torch.from_numpy(g).to(torch.bfloat16)
+    assert np.array_equal(g_f16.astype(np.float32), g)
+    assert np.array_equal(g_bf16.to(torch.float32).numpy(), g)
+    p1, a1, b1 = master.copy(), m.copy(), v.copy()
+    p2, a2, b2 = master.copy(), m.copy(), v.copy()
+    w1 = np.zeros(n, dtype=np.uint16)
+    w2 = np.zeros(n, dtype=np.uint16)
+    oracle.adam_f32(_bits(g_bf16), p1, a1, b1, w1, **HP)
+    bad = oracle.adam_f32_f16(g_f16.view(np.uint16).copy(), 1.0, p2, a2, b2, w2, **HP)
+    assert bad == 0
+    for x, y in ((p1, p2), (a1, a2), (b1, b2)):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+    # a power-of-two loss scale changes nothing either: g*S is exact in fp16 here, and g*S/S is g
+    p3, a3, b3 = master.copy(), m.copy(), v.copy()
+    w3 = np.zeros(n, dtype=np.uint16)
+    oracle.adam_f32_f16((g * 8).astype(np.float16).view(np.uint16).copy(), 0.125, p3, a3, b3, w3, **HP)
+    for x, y in ((p1, p3), (a1, a3), (b1, b3)):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+    assert np.array_equal(w2, w3)
+
+
+def test_f16_step_counts_nonfinite_gradients(oracle):
+    n = 1000
+    master, m, v, gb = _draw_f16(n, 3, 256.0)
+    gb[[5, 17, 900]] = [0x7C00, 0xFC00, 0x7E01]         # +inf, -inf, NaN
+    w16 = np.zeros(n, dtype=np.uint16)
+    p, a, b = master.copy(), m.copy(), v.copy()
+    bad = oracle.adam_f32_f16(gb, 1.0 / 256, p, a, b, w16, **HP)
+    assert bad == 3
+    ok = np.ones(n, dtype=bool)
+    ok[[5, 17, 900]] = False
+    assert np.isfinite(p[ok]).all() and np.isfinite(a[ok]).all() and np.isfinite(b[ok]).all()
+    assert not np.isfinite(a[5]) and not np.isfinite(a[17]) and np.isnan(a[900])
