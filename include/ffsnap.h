@@ -53,12 +53,12 @@ typedef enum {
     FF_ERR_HOST_ONLY = -6 /* device work asked of a plan built with FF_PLAN_HOST_ONLY           */
 } ff_status;
 
-typedef enum { FF_BF16 = 1, FF_F32 = 2 } ff_dtype;
+typedef enum { FF_BF16 = 1, FF_F32 = 2, FF_F16 = 3 } ff_dtype;
 
 /* Role of a segment in the fused optimizer step; RAW segments are only ever copied. */
 typedef enum {
     FF_KIND_RAW = 0,
-    FF_KIND_W16 = 1,    /* bf16 working weights            */
+    FF_KIND_W16 = 1,    /* 16-bit working weights: bf16, or fp16 (one format per plan) */
     FF_KIND_MASTER = 2, /* fp32 master weights             */
     FF_KIND_M = 3,      /* fp32 Adam first moment          */
     FF_KIND_V = 4       /* fp32 Adam second moment         */
@@ -225,6 +225,24 @@ typedef struct {
  */
 int ff_adam_step_snapshot(const ff_plan *plan, const void *const *grads, const ff_adam_hparams *hp,
                           void *chunks, uint32_t *crcs, void *hip_stream);
+
+/*
+ * The same step for fp16 training with a loss scale (section 7.1: the evaluated models train in
+ * fp16).  The plan's working weights are FF_F16; grads point to fp16 gradients of a loss that
+ * was multiplied by S, and inv_loss_scale = 1/S:
+ *     g = float(grad) * inv_loss_scale   (one rounded fp32 multiplication)
+ * then the arithmetic of ff_adam_step_snapshot, and w' = fp16_rne(p') (overflow gives infinity;
+ * NaN keeps its sign and top 9 payload bits and is quiet).  n_nonfinite: DEVICE, one uint64,
+ * 8-byte aligned, or NULL: receives the number of gradient elements that are infinite or NaN.
+ * The update is applied to every element regardless; a caller that lowers S on overflow goes
+ * back to the previous snapshot (the paper keeps the two most recent ones, section 4.2).
+ * FF_ERR_INVALID also if the plan's working weights are bf16 (and ff_adam_step_snapshot
+ * returns it for an fp16 plan).
+ */
+int ff_adam_step_snapshot_f16(const ff_plan *plan, const void *const *grads,
+                              const ff_adam_hparams *hp, float inv_loss_scale,
+                              uint64_t *n_nonfinite, void *chunks, uint32_t *crcs,
+                              void *hip_stream);
 
 /* Test helper: CRC32C of nbytes at dev_buf (DEVICE, 16-byte aligned) into *dev_out (DEVICE),
  * computed by the same tile and combine kernels as ff_pack.  Allocates and frees a small

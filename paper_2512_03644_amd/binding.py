@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libffsnap.so")
 
 FF_OK, FF_ERR_NULL, FF_ERR_INVALID, FF_ERR_EMPTY = 0, -1, -2, -3
 FF_ERR_NOMEM, FF_ERR_HIP, FF_ERR_HOST_ONLY = -4, -5, -6
-FF_BF16, FF_F32 = 1, 2
+FF_BF16, FF_F32, FF_F16 = 1, 2, 3
 FF_KIND_RAW, FF_KIND_W16, FF_KIND_MASTER, FF_KIND_M, FF_KIND_V = 0, 1, 2, 3, 4
 FF_PLAN_HOST_ONLY = 1
 FF_RESTORE_VERIFY_ONLY = 1
@@ -23,7 +23,8 @@ FF_RESTORE_SKIP_BAD = 2
 EXPORTS = ["ff_snapshot_plan", "ff_plan_destroy", "ff_plan_payload_bytes", "ff_plan_num_chunks",
            "ff_plan_buffer_bytes", "ff_plan_chunk_bytes", "ff_plan_num_segments",
            "ff_plan_num_params", "ff_plan_layout_id", "ff_plan_segment_range",
-           "ff_plan_chunk_span", "ff_razor_select", "ff_pack", "ff_pack_to_host", "ff_restore", "ff_restore_chunks", "ff_adam_step_snapshot", "ff_crc32c", "ff_copy_ceiling", "ff_strerror"]
+           "ff_plan_chunk_span", "ff_razor_select", "ff_pack", "ff_pack_to_host", "ff_restore", "ff_restore_chunks", "ff_adam_step_snapshot",
+           "ff_adam_step_snapshot_f16", "ff_crc32c", "ff_copy_ceiling", "ff_strerror"]
 
 
 class ff_segment(ctypes.Structure):
@@ -90,6 +91,10 @@ def lib():
         L.ff_adam_step_snapshot.restype = i32
         L.ff_adam_step_snapshot.argtypes = [vp, ctypes.POINTER(vp),
                                             ctypes.POINTER(ff_adam_hparams), vp, vp, vp]
+        L.ff_adam_step_snapshot_f16.restype = i32
+        L.ff_adam_step_snapshot_f16.argtypes = [vp, ctypes.POINTER(vp),
+                                                ctypes.POINTER(ff_adam_hparams), ctypes.c_float,
+                                                vp, vp, vp, vp]
         L.ff_crc32c.restype, L.ff_crc32c.argtypes = i32, [vp, u64, vp, vp]
         L.ff_copy_ceiling.restype, L.ff_copy_ceiling.argtypes = i32, [vp, vp, u64, vp]
         L.ff_strerror.restype, L.ff_strerror.argtypes = ctypes.c_char_p, [i32]
@@ -112,7 +117,7 @@ def _stream_ptr(stream):
     return ctypes.c_void_p(stream.cuda_stream)
 
 
-_DTYPES = {torch.bfloat16: FF_BF16, torch.float32: FF_F32}
+_DTYPES = {torch.bfloat16: FF_BF16, torch.float32: FF_F32, torch.float16: FF_F16}
 
 
 def make_segments(tensors, kinds=None, param_ids=None):
@@ -234,6 +239,19 @@ def ff_adam_step_snapshot(plan, grads, hparams, chunks, crcs, stream=None):
                          hparams["weight_decay"], hparams["step"])
     _check(lib().ff_adam_step_snapshot(plan.handle, ptrs, ctypes.byref(hp), chunks.data_ptr(),
                                        crcs.data_ptr(), _stream_ptr(stream)))
+
+
+def ff_adam_step_snapshot_f16(plan, grads, hparams, inv_loss_scale, n_nonfinite, chunks, crcs,
+                              stream=None):
+    """grads: list of fp16 device tensors (gradients of the scaled loss); n_nonfinite: one-element
+    int64 device tensor, or None."""
+    ptrs = (ctypes.c_void_p * max(len(grads), 1))(*[g.data_ptr() for g in grads])
+    hp = ff_adam_hparams(hparams["lr"], hparams["beta1"], hparams["beta2"], hparams["eps"],
+                         hparams["weight_decay"], hparams["step"])
+    _check(lib().ff_adam_step_snapshot_f16(
+        plan.handle, ptrs, ctypes.byref(hp), ctypes.c_float(inv_loss_scale),
+        ctypes.c_void_p(n_nonfinite.data_ptr()) if n_nonfinite is not None else None,
+        chunks.data_ptr(), crcs.data_ptr(), _stream_ptr(stream)))
 
 
 def ff_crc32c(buf, nbytes, out, stream=None):

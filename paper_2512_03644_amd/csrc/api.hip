@@ -312,6 +312,54 @@ int check_restore_args(const ff_plan* p, const void* chunks, const uint32_t* crc
     return FF_OK;
 }
 
+int adam_impl(const ff_plan* p, const void* const* grads, const ff_adam_hparams* hp,
+              uint32_t half_dtype, float inv_scale, uint64_t* n_nonfinite, void* chunks,
+              uint32_t* crcs, hipStream_t s)
+{
+    int rc = check_device_call(p);
+    if (rc != FF_OK) return rc;
+    if (!grads || !hp || !chunks || !crcs) return FF_ERR_NULL;
+    const Layout& L = p->layout;
+    if (!L.adam_ok || L.params.empty() || hp->step == 0) return FF_ERR_INVALID;
+    if (L.half_dtype != half_dtype) return FF_ERR_INVALID;  // bf16 plan <-> fp16 call or vice versa
+    if (reinterpret_cast<uint64_t>(chunks) % 16 || reinterpret_cast<uint64_t>(crcs) % 4)
+        return FF_ERR_INVALID;
+    for (size_t i = 0; i < L.params.size(); i++) {
+        if (!grads[i]) return FF_ERR_NULL;
+        if (reinterpret_cast<uint64_t>(grads[i]) % 2) return FF_ERR_INVALID;
+    }
+    FusedConsts c;
+    {
+        // shared scalars: evaluated in double from the fp32 hyper-parameters, rounded once
+        const double lr = hp->lr, b1 = hp->beta1, b2 = hp->beta2, wd = hp->weight_decay;
+        const double t = static_cast<double>(hp->step);
+        c.adam.decay = static_cast<float>(1.0 - lr * wd);
+        c.adam.b1 = hp->beta1;
+        c.adam.omb1 = static_cast<float>(1.0 - b1);
+        c.adam.b2 = hp->beta2;
+        c.adam.omb2 = static_cast<float>(1.0 - b2);
+        c.adam.step_size = static_cast<float>(lr / (1.0 - std::pow(b1, t)));
+        c.adam.bc2s = static_cast<float>(std::sqrt(1.0 - std::pow(b2, t)));
+        c.adam.eps = hp->eps;
+    }
+    c.inv_scale = inv_scale;
+    c.n_nonfinite = n_nonfinite;
+    // the pointer array is copied into the plan first: the asynchronous upload reads from there
+    try {
+        p->host_grads.resize(L.params.size());
+    } catch (const std::bad_alloc&) {
+        return FF_ERR_NOMEM;
+    }
+    for (size_t i = 0; i < L.params.size(); i++)
+        p->host_grads[i] = reinterpret_cast<uint64_t>(grads[i]);
+    FF_HIP_TRY(hipMemcpyAsync(p->grads, p->host_grads.data(), L.params.size() * sizeof(uint64_t),
+                              hipMemcpyHostToDevice, s));
+    FF_HIP_TRY(launch_fused(half_dtype == FF_F16, p->work, p->n_work, p->grads, p->fused_tabs,
+                            chunks, crcs, L.n_chunks, L.payload, L.buffer_bytes, p->affine, c, s));
+    return FF_OK;
+}
+
+
 }  // namespace
 
 extern "C" {
@@ -428,45 +476,18 @@ int ff_plan_chunk_span(const ff_plan* p, uint64_t chunk, uint64_t* first_seg, ui
 int ff_adam_step_snapshot(const ff_plan* p, const void* const* grads, const ff_adam_hparams* hp,
                           void* chunks, uint32_t* crcs, void* hip_stream)
 {
-    int rc = check_device_call(p);
-    if (rc != FF_OK) return rc;
-    if (!grads || !hp || !chunks || !crcs) return FF_ERR_NULL;
-    const Layout& L = p->layout;
-    if (!L.adam_ok || L.params.empty() || hp->step == 0) return FF_ERR_INVALID;
-    if (reinterpret_cast<uint64_t>(chunks) % 16 || reinterpret_cast<uint64_t>(crcs) % 4)
-        return FF_ERR_INVALID;
-    for (size_t i = 0; i < L.params.size(); i++) {
-        if (!grads[i]) return FF_ERR_NULL;
-        if (reinterpret_cast<uint64_t>(grads[i]) % 2) return FF_ERR_INVALID;
-    }
-    FusedConsts c;
-    {
-        // shared scalars: evaluated in double from the fp32 hyper-parameters, rounded once
-        const double lr = hp->lr, b1 = hp->beta1, b2 = hp->beta2, wd = hp->weight_decay;
-        const double t = static_cast<double>(hp->step);
-        c.adam.decay = static_cast<float>(1.0 - lr * wd);
-        c.adam.b1 = hp->beta1;
-        c.adam.omb1 = static_cast<float>(1.0 - b1);
-        c.adam.b2 = hp->beta2;
-        c.adam.omb2 = static_cast<float>(1.0 - b2);
-        c.adam.step_size = static_cast<float>(lr / (1.0 - std::pow(b1, t)));
-        c.adam.bc2s = static_cast<float>(std::sqrt(1.0 - std::pow(b2, t)));
-        c.adam.eps = hp->eps;
-    }
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    // the pointer array is copied into the plan first: the asynchronous upload reads from there
-    try {
-        p->host_grads.resize(L.params.size());
-    } catch (const std::bad_alloc&) {
-        return FF_ERR_NOMEM;
-    }
-    for (size_t i = 0; i < L.params.size(); i++)
-        p->host_grads[i] = reinterpret_cast<uint64_t>(grads[i]);
-    FF_HIP_TRY(hipMemcpyAsync(p->grads, p->host_grads.data(), L.params.size() * sizeof(uint64_t),
-                              hipMemcpyHostToDevice, s));
-    FF_HIP_TRY(launch_fused(p->work, p->n_work, p->grads, p->fused_tabs, chunks, crcs, L.n_chunks,
-                            L.payload, L.buffer_bytes, p->affine, c, s));
-    return FF_OK;
+    return adam_impl(p, grads, hp, FF_BF16, 1.0f, nullptr, chunks, crcs,
+                     static_cast<hipStream_t>(hip_stream));
+}
+
+int ff_adam_step_snapshot_f16(const ff_plan* p, const void* const* grads,
+                              const ff_adam_hparams* hp, float inv_loss_scale,
+                              uint64_t* n_nonfinite, void* chunks, uint32_t* crcs,
+                              void* hip_stream)
+{
+    if (reinterpret_cast<uint64_t>(n_nonfinite) % 8) return FF_ERR_INVALID;
+    return adam_impl(p, grads, hp, FF_F16, inv_loss_scale, n_nonfinite, chunks, crcs,
+                     static_cast<hipStream_t>(hip_stream));
 }
 
 int ff_crc32c(const void* dev_buf, uint64_t nbytes, uint32_t* dev_out, void* hip_stream)

@@ -15,6 +15,8 @@
 // of the last chunk; a finish kernel adds the preset/complement term.
 #include "fused.hpp"
 
+#include <hip/hip_fp16.h>
+
 #include "fold.h"
 
 namespace ffsnap {
@@ -43,12 +45,29 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// fp32 -> fp16 bits: the hardware conversion rounds to nearest even, overflows to infinity and
+// produces subnormals; NaN is given a fixed form (sign, top 9 payload bits, quiet).
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float f)
+{
+    const uint32_t u = f32_to_bits(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return ((u >> 16) & 0x8000u) | 0x7E00u | ((u >> 13) & 0x1FFu);
+    return __half_as_ushort(__float2half_rn(f));
+}
+
 // One element of the update; every operation is a separately rounded fp32 operation (the file
 // is compiled with -ffp-contract=off, division and square root are correctly rounded).
-__device__ __forceinline__ void adam_element(const AdamConsts& k, uint32_t g_bits, float& p,
+// F16: the gradient is fp16 of a loss scaled by S and is multiplied by inv_scale = 1/S first;
+// the working weight is rounded to fp16.  Otherwise both are bf16 and nothing is scaled.
+template <bool F16>
+__device__ __forceinline__ void adam_element(const FusedConsts& C, uint32_t g_bits, float& p,
                                              float& m, float& v, uint32_t& w_bits)
 {
-    const float g = bits_to_f32(g_bits << 16);
+    const AdamConsts& k = C.adam;
+    float g;
+    if constexpr (F16)
+        g = __half2float(__ushort_as_half(static_cast<unsigned short>(g_bits))) * C.inv_scale;
+    else
+        g = bits_to_f32(g_bits << 16);
     const float pd = p * k.decay;
     const float m1 = (k.b1 * m) + (k.omb1 * g);
     const float v1 = (k.b2 * v) + ((k.omb2 * g) * g);
@@ -60,8 +79,11 @@ __device__ __forceinline__ void adam_element(const AdamConsts& k, uint32_t g_bit
     p = p1;
     m = m1;
     v = v1;
-    w_bits = f32_to_bf16_bits(p1);
+    w_bits = F16 ? f32_to_f16_bits(p1) : f32_to_bf16_bits(p1);
 }
+
+// fp16 infinity or NaN
+__device__ __forceinline__ bool f16_nonfinite(uint32_t bits) { return (bits & 0x7C00u) == 0x7C00u; }
 
 struct Lds {
     uint32_t tab16[1024];  // multiply by x^8192  (1 KiB rows)
@@ -126,6 +148,7 @@ __device__ __forceinline__ TileGeom tile_geom(const WorkTile& t)
 }
 
 // Update wavefront `u` (0..3): rows u - pad_rows, u - pad_rows + 4, ...
+template <bool F16>
 __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G,
                                             const uint8_t* __restrict__ grad,
                                             uint8_t* __restrict__ chunks,
@@ -156,6 +179,7 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
         }
     };
 
+    uint32_t nonfinite = 0;  // this lane's count of infinite or NaN gradient elements (fp16 only)
     RowIn q0, q1;  // inputs of this wavefront's next two rows
     q0 = q1 = RowIn{u32x2{0, 0}, u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}};
     load_row(u - G.pad_rows, q0);
@@ -183,7 +207,10 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
                     v[0] = bits_to_f32(cur.v.x); v[1] = bits_to_f32(cur.v.y);
                     v[2] = bits_to_f32(cur.v.z); v[3] = bits_to_f32(cur.v.w);
 #pragma unroll
-                    for (int s = 0; s < 4; s++) adam_element(C.adam, gb[s], p[s], m[s], v[s], wb[s]);
+                    for (int s = 0; s < 4; s++) {
+                        if constexpr (F16) nonfinite += f16_nonfinite(gb[s]) ? 1u : 0u;
+                        adam_element<F16>(C, gb[s], p[s], m[s], v[s], wb[s]);
+                    }
                     const u32x2 w2 = {wb[0] | (wb[1] << 16), wb[2] | (wb[3] << 16)};
                     const u32x4 po = {f32_to_bits(p[0]), f32_to_bits(p[1]), f32_to_bits(p[2]), f32_to_bits(p[3])};
                     const u32x4 mo = {f32_to_bits(m[0]), f32_to_bits(m[1]), f32_to_bits(m[2]), f32_to_bits(m[3])};
@@ -207,7 +234,8 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
                             p[s] = *as_global(reinterpret_cast<const float*>(tp + 4 * j));
                             m[s] = *as_global(reinterpret_cast<const float*>(tm + 4 * j));
                             v[s] = *as_global(reinterpret_cast<const float*>(tv + 4 * j));
-                            adam_element(C.adam, gb[s], p[s], m[s], v[s], wb[s]);
+                            if constexpr (F16) nonfinite += f16_nonfinite(gb[s]) ? 1u : 0u;
+                            adam_element<F16>(C, gb[s], p[s], m[s], v[s], wb[s]);
                             *as_global(reinterpret_cast<uint16_t*>(tw + 2 * j)) = static_cast<uint16_t>(wb[s]);
                             *as_global(reinterpret_cast<float*>(tp + 4 * j)) = p[s];
                             *as_global(reinterpret_cast<float*>(tm + 4 * j)) = m[s];
@@ -264,6 +292,15 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
             *reinterpret_cast<u32x4*>(&out.v[u][4 * lane]) = u32x4{fv[0], fv[1], fv[2], fv[3]};
         }
         __syncthreads();
+    }
+    if constexpr (F16) {
+        if (C.n_nonfinite) {
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) nonfinite += __shfl_xor(nonfinite, d);
+            if (lane == 0 && nonfinite)
+                atomicAdd(reinterpret_cast<unsigned long long*>(C.n_nonfinite),
+                          static_cast<unsigned long long>(nonfinite));
+        }
     }
 }
 
@@ -348,6 +385,7 @@ __device__ __forceinline__ void run_raw_tile(const WorkTile& t, uint8_t* __restr
     if (lane == 0) add_piece(crcs, t, 0, reg);
 }
 
+template <bool F16>
 __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
     const WorkTile* __restrict__ tiles, uint32_t n_tiles, const uint64_t* __restrict__ grads,
     const uint32_t* __restrict__ tabs, uint8_t* __restrict__ chunks, uint32_t* __restrict__ crcs,
@@ -385,7 +423,7 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
     const TileGeom G = tile_geom(t);
     if (wave < kUpdateWaves) {
         const uint8_t* grad = reinterpret_cast<const uint8_t*>(grads[t.grad_index]);
-        update_role(t, G, grad, chunks, crcs, C, buf, wave, lane);
+        update_role<F16>(t, G, grad, chunks, crcs, C, buf, wave, lane);
     } else {
         const int x = wave - kUpdateWaves;
         uint32_t reg;
@@ -397,12 +435,13 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
     }
 }
 
-// crcs[] = 0 and the tail of the last chunk = 0
+// crcs[] = 0, the tail of the last chunk = 0, and the non-finite gradient counter = 0
 __global__ void fused_prepare_kernel(uint32_t* __restrict__ crcs, uint64_t n_chunks,
                                      uint8_t* __restrict__ chunks, uint64_t payload,
-                                     uint64_t buffer_bytes)
+                                     uint64_t buffer_bytes, uint64_t* __restrict__ n_nonfinite)
 {
     const uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i == 0 && n_nonfinite) *n_nonfinite = 0;
     const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
     for (uint64_t j = i; j < n_chunks; j += stride) crcs[j] = 0;
     uint16_t* tail = reinterpret_cast<uint16_t*>(chunks + payload);  // payload is even
@@ -430,7 +469,7 @@ void build_fused_tabs(uint32_t* tab)
     }
 }
 
-hipError_t launch_fused(const WorkTile* tiles, uint32_t n_tiles, const uint64_t* grads,
+hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_tiles, const uint64_t* grads,
                         const uint32_t* tabs, void* chunks, uint32_t* crcs, uint64_t n_chunks,
                         uint64_t payload, uint64_t buffer_bytes, uint32_t affine,
                         const FusedConsts& consts, hipStream_t stream)
@@ -442,13 +481,17 @@ hipError_t launch_fused(const WorkTile* tiles, uint32_t n_tiles, const uint64_t*
     if (prep_blocks == 0) prep_blocks = 1;
     if (prep_blocks > 4096) prep_blocks = 4096;
     hipLaunchKernelGGL(fused_prepare_kernel, dim3(prep_blocks), dim3(256), 0, stream, crcs, n_chunks,
-                       c, payload, buffer_bytes);
+                       c, payload, buffer_bytes, f16 ? consts.n_nonfinite : nullptr);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (n_tiles) {
         const unsigned grid = n_tiles;
-        hipLaunchKernelGGL(fused_kernel, dim3(grid), dim3(kWaveSize * kWavesPerBlock), 0, stream,
-                           tiles, n_tiles, grads, tabs, c, crcs, consts);
+        if (f16)
+            hipLaunchKernelGGL(fused_kernel<true>, dim3(grid), dim3(kWaveSize * kWavesPerBlock), 0,
+                               stream, tiles, n_tiles, grads, tabs, c, crcs, consts);
+        else
+            hipLaunchKernelGGL(fused_kernel<false>, dim3(grid), dim3(kWaveSize * kWavesPerBlock), 0,
+                               stream, tiles, n_tiles, grads, tabs, c, crcs, consts);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

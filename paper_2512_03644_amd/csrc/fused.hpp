@@ -14,6 +14,8 @@ struct AdamConsts {
 
 struct FusedConsts {
     AdamConsts adam;
+    float inv_scale = 1.0f;            // fp16 variant: reciprocal of the loss scale
+    uint64_t* n_nonfinite = nullptr;   // fp16 variant: device counter of inf/NaN gradients, or null
 };
 
 // Device table of the fused kernels (kFusedTabWords entries): byte tables of multiplication by
@@ -24,7 +26,8 @@ void build_fused_tabs(uint32_t* tab);
 
 // Enqueues prepare (crcs = 0, zero tail), the tile kernel and finish (crcs ^= affine).
 // tiles/grads/tabs: device tables (tabs = tables for 1024-byte rows, then for 512-byte rows).
-hipError_t launch_fused(const WorkTile* tiles, uint32_t n_tiles, const uint64_t* grads,
+// f16: gradients and working weights are fp16 (else bf16).
+hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_tiles, const uint64_t* grads,
                         const uint32_t* tabs, void* chunks, uint32_t* crcs, uint64_t n_chunks,
                         uint64_t payload, uint64_t buffer_bytes, uint32_t affine,
                         const FusedConsts& consts, hipStream_t stream);

@@ -22,9 +22,9 @@ int build_layout(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_bytes, 
     uint64_t off = 0;
     for (uint64_t i = 0; i < n_segs; i++) {
         const ff_segment& s = segs[i];
-        if (s.dtype != FF_BF16 && s.dtype != FF_F32) return FF_ERR_INVALID;
+        if (s.dtype != FF_BF16 && s.dtype != FF_F32 && s.dtype != FF_F16) return FF_ERR_INVALID;
         if (s.kind > FF_KIND_V || s.reserved != 0) return FF_ERR_INVALID;
-        const uint64_t es = (s.dtype == FF_BF16) ? 2 : 4;
+        const uint64_t es = (s.dtype == FF_F32) ? 4 : 2;
         if (s.nbytes % es) return FF_ERR_INVALID;
         if (s.nbytes == 0) continue;  // empty segments take no place in the stream
         if (!s.ptr) return FF_ERR_NULL;
@@ -61,8 +61,14 @@ int build_layout(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_bytes, 
             int32_t& slot = it->second.seg[s.kind - 1];
             if (slot >= 0) ok = false;  // the same role twice
             slot = static_cast<int32_t>(i);
-            const bool want_bf16 = (s.kind == FF_KIND_W16);
-            if ((s.dtype == FF_BF16) != want_bf16) ok = false;
+            // working weights are 16-bit, of one format throughout the plan; the rest is fp32
+            if (s.kind == FF_KIND_W16) {
+                if (s.dtype == FF_F32) ok = false;
+                if (L.half_dtype == 0) L.half_dtype = s.dtype;
+                if (s.dtype != L.half_dtype) ok = false;
+            } else if (s.dtype != FF_F32) {
+                ok = false;
+            }
         }
         for (auto& kv : groups) {
             Param& p = kv.second;

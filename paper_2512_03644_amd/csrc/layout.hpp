@@ -27,6 +27,7 @@ struct Layout {
     std::vector<Seg> segs;      // non-empty segments, stream order
     std::vector<Param> params;  // ascending param_id
     bool adam_ok = false;       // every non-RAW segment belongs to a complete, consistent group
+    uint32_t half_dtype = 0;    // format of the working weights: FF_BF16 or FF_F16 (0: no groups)
     uint32_t layout_id = 0;
     // tiling: a tile is the stream range one wavefront folds; it never crosses a chunk
     uint64_t tile_bytes = 0, n_tiles = 0;

@@ -101,23 +101,24 @@ def _normal(n, std, gen, device):
 
 
 def param_shard(name, numels, chunk_bytes, seed, device="cpu", with_grads=False,
-                tiny_recipe=False):
+                tiny_recipe=False, half=torch.bfloat16, loss_scale=1.0):
     """Parameter-major shard.  tiny_recipe: weight, master, m, v each ~N(0, 0.02) (the small
     correctness configuration).  Otherwise the training-like recipe: master ~N(0, 0.02),
-    w16 = bf16(master), m ~N(0, 1e-3), v = N(0, 1e-3)^2 >= 0, grads (bf16) ~N(0, 1e-3)."""
+    w16 = half(master), m ~N(0, 1e-3), v = N(0, 1e-3)^2 >= 0, grads ~N(0, 1e-3) * loss_scale in
+    the 16-bit format `half` (bf16, or fp16 for the loss-scaled variant)."""
     gen = _gen(device, seed)
     segs, params = [], []
     for n in numels:
         master = _normal(n, 0.02, gen, device)
         if tiny_recipe:
-            w16 = _normal(n, 0.02, gen, device).to(torch.bfloat16)
+            w16 = _normal(n, 0.02, gen, device).to(half)
             m = _normal(n, 0.02, gen, device)
             v = _normal(n, 0.02, gen, device)
         else:
-            w16 = master.to(torch.bfloat16)
+            w16 = master.to(half)
             m = _normal(n, 1e-3, gen, device)
             v = _normal(n, 1e-3, gen, device).square_()
-        grad = _normal(n, 1e-3, gen, device).to(torch.bfloat16) if with_grads else None
+        grad = (_normal(n, 1e-3, gen, device) * loss_scale).to(half) if with_grads else None
         params.append(ParamGroup(w16, master, m, v, grad))
         segs += [w16, master, m, v]
     return Shard(name, chunk_bytes, segs, params)
@@ -152,9 +153,10 @@ def config_tiny(device="cpu"):
     return param_shard("tiny-64", tiny_numels(), 1 * MiB, SEED_BASE + 1, device, tiny_recipe=True)
 
 
-def config_llama7b(device, with_grads=False):
+def config_llama7b(device, with_grads=False, half=torch.bfloat16, loss_scale=1.0):
     return param_shard("llama7b-dp8", llama7b_dp8_numels(), 4 * MiB,
-                       SEED_BASE + (4 if with_grads else 2), device, with_grads=with_grads)
+                       SEED_BASE + (4 if with_grads else 2), device, with_grads=with_grads,
+                       half=half, loss_scale=loss_scale)
 
 
 def config_fragmented(device="cpu", n_tensors=20000, max_numel=4 * MiB):

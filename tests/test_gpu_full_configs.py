@@ -146,6 +146,42 @@ def test_config4_fused_adam_full(oracle):
                           _sample(plan, len(shard.segments), rng, k=8))
 
 
+def test_config4_fused_adam_full_fp16(oracle):
+    """The same shard in fp16 with a loss scale of 65536 (the paper's models train in fp16)."""
+    scale = 65536.0
+    shard = wl.config_llama7b(DEV, with_grads=True, half=torch.float16, loss_scale=scale)
+    plan = ff.plan_for_shard(shard)
+    hp = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1000)
+    inv = float(np.float32(1.0 / scale))
+    sample = [0, 3, 111, 225]
+    host = {}
+    for i in sample:
+        p = shard.params[i]
+        host[i] = [wl.to_numpy_bytes(t) for t in (p.w16, p.master, p.m, p.v, p.grad)]
+    chunks, crcs, bad, n_bad = ff.alloc_outputs(plan, DEV)
+    n_nonfinite = torch.full((1,), -1, dtype=torch.int64, device=DEV)
+    ff.ff_adam_step_snapshot_f16(plan, [p.grad for p in shard.params], hp, inv, n_nonfinite,
+                                 chunks, crcs)
+    torch.cuda.synchronize()
+    # N(0, 1e-3) * 65536 has sigma 65.5: an fp16 overflow would be a 1000-sigma event
+    assert int(n_nonfinite.item()) == 0
+    for i in sample:
+        w16, master, m, v, g = host[i]
+        nb = oracle.adam_f32_f16(g.view(np.uint16), inv, master.view(np.float32),
+                                 m.view(np.float32), v.view(np.float32), w16.view(np.uint16), **hp)
+        assert nb == 0
+        p = shard.params[i]
+        for got_t, want in ((p.w16, w16), (p.master, master), (p.m, m), (p.v, v)):
+            assert np.array_equal(wl.to_numpy_bytes(got_t), want), i
+    for p in shard.params[::17]:
+        assert torch.equal(p.w16, p.master.to(torch.float16))
+    chunks2, crcs2, _, _ = ff.alloc_outputs(plan, DEV)
+    ff.ff_pack(plan, chunks2, crcs2)
+    torch.cuda.synchronize()
+    assert torch.equal(crcs, crcs2)
+    assert torch.equal(chunks, chunks2)
+
+
 def test_config5_llama70b_verified_restore(oracle):
     shard = wl.config_llama70b(DEV)
     plan = ff.plan_for_shard(shard)

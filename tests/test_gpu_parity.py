@@ -226,12 +226,15 @@ def test_pack_on_a_side_stream(oracle):
 HP = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1000)
 
 
-def _adam_and_compare(oracle, numels, chunk, seed, hp=HP, extra_raw=None):
+def _adam_and_compare(oracle, numels, chunk, seed, hp=HP, extra_raw=None, half=torch.bfloat16,
+                      loss_scale=1.0):
     """Runs ff_adam_step_snapshot and the oracle's unfused definition (update, then pack) on the
     same inputs.  fp32 state: max relative error <= 1e-6 is the acceptance bound; the fixed
-    operation order makes the two bit-identical, which is what is asserted.  bf16 weights: exact
-    rounding of the GPU's own fp32 master.  Snapshot bytes and CRCs: bit-exact."""
-    shard = wl.param_shard("a", numels, chunk, seed, DEV, with_grads=True)
+    operation order makes the two bit-identical, which is what is asserted.  16-bit weights: exact
+    rounding of the GPU's own fp32 master.  Snapshot bytes and CRCs: bit-exact.
+    half = torch.float16 runs the loss-scaled fp16 variant of both."""
+    shard = wl.param_shard("a", numels, chunk, seed, DEV, with_grads=True, half=half,
+                           loss_scale=loss_scale)
     tensors = list(shard.segments)
     kinds, pids = [], []
     for pid in range(len(shard.params)):
@@ -255,18 +258,28 @@ def _adam_and_compare(oracle, numels, chunk, seed, hp=HP, extra_raw=None):
     chunks, crcs, bad, n_bad = ff.alloc_outputs(plan, DEV)
     chunks.fill_(0xA5)
     crcs.fill_(-1)
-    ff.ff_adam_step_snapshot(plan, [p.grad for p in shard.params], hp, chunks, crcs)
-    torch.cuda.synchronize()
-    want_buf, want_crcs = oracle.adam_snapshot(params_np, grads_np, host, chunk, hp, threads=8)
+    if half == torch.float16:
+        inv = float(np.float32(1.0 / loss_scale))
+        n_nonfinite = torch.full((1,), -1, dtype=torch.int64, device=DEV)
+        ff.ff_adam_step_snapshot_f16(plan, [p.grad for p in shard.params], hp, inv, n_nonfinite,
+                                     chunks, crcs)
+        torch.cuda.synchronize()
+        want_buf, want_crcs, want_bad = oracle.adam_snapshot_f16(params_np, grads_np, inv, host,
+                                                                 chunk, hp, threads=8)
+        assert int(n_nonfinite.item()) == want_bad == 0
+    else:
+        ff.ff_adam_step_snapshot(plan, [p.grad for p in shard.params], hp, chunks, crcs)
+        torch.cuda.synchronize()
+        want_buf, want_crcs = oracle.adam_snapshot(params_np, grads_np, host, chunk, hp, threads=8)
     for p, (w16, master, m, v) in zip(shard.params, params_np):
         for name, got_t, want in (("master", p.master, master), ("m", p.m, m), ("v", p.v, v)):
             got = got_t.cpu().numpy()
             rel = np.abs(got.astype(np.float64) - want) / np.maximum(np.abs(want), 1.1754944e-38)
             assert rel.max(initial=0.0) <= 1e-6, name
             assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), name
-        # bf16 weight: exact RNE of the GPU's own fp32 master
+        # 16-bit weight: exact RNE of the GPU's own fp32 master
         got_w = wl.to_numpy_bytes(p.w16).view(np.uint16)
-        assert np.array_equal(got_w, wl.to_numpy_bytes(p.master.to(torch.bfloat16)).view(np.uint16))
+        assert np.array_equal(got_w, wl.to_numpy_bytes(p.master.to(half)).view(np.uint16))
         assert np.array_equal(got_w, w16)
     assert np.array_equal(chunks.cpu().numpy(), want_buf)
     assert np.array_equal(_u32(crcs), want_crcs)
@@ -360,6 +373,104 @@ def test_fused_adam_argument_errors():
         ff.ff_adam_step_snapshot(raw, [p.grad], HP, chunks, crcs)
     assert e.value.status == ff.FF_ERR_INVALID
 
+
+
+# ---- fp16 variant of the fused step ---------------------------------------------------------------
+
+@pytest.mark.parametrize("chunk,loss_scale", [(1024, 1.0), (4096, 1024.0), (1 << 16, 65536.0),
+                                              (1 << 20, 128.0)])
+def test_fused_adam_f16_small_ragged(oracle, chunk, loss_scale):
+    numels = [1, 3, 255, 256, 257, 1000, 4097, 70001, 131072, 65536 + 255, 5, 77]
+    _adam_and_compare(oracle, numels, chunk, seed=chunk + 1, half=torch.float16,
+                      loss_scale=loss_scale)
+
+
+@pytest.mark.parametrize("step", [1, 2, 1000])
+def test_fused_adam_f16_steps_and_hparams(oracle, step):
+    hp = dict(lr=1e-3, beta1=0.8, beta2=0.999, eps=1e-6, weight_decay=0.0, step=step)
+    _adam_and_compare(oracle, [5000, 12345, 300], 4096, seed=step, hp=hp, half=torch.float16,
+                      loss_scale=4096.0)
+
+
+def test_fused_adam_f16_with_raw_segments(oracle):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(3)
+    raw1 = torch.randn(3001, device=DEV, generator=g)
+    raw2 = torch.randn(70000, device=DEV, generator=g).to(torch.float16)
+    _adam_and_compare(oracle, [1000, 33333, 77], 4096, seed=9, extra_raw=[(0, raw1), (5, raw2)],
+                      half=torch.float16, loss_scale=512.0)
+
+
+def test_fused_adam_f16_nonfinite_gradients_and_weight_overflow(oracle):
+    n = 5000
+    shard = wl.param_shard("a", [n, 300], 4096, 6, DEV, with_grads=True, half=torch.float16,
+                           loss_scale=1024.0)
+    p = shard.params[0]
+    inf = float("inf")
+    p.grad[:6] = torch.tensor([inf, -inf, float("nan"), 65504.0, -65504.0, 6e-8], device=DEV).to(torch.float16)
+    p.grad[4097] = inf                                   # second tile row range, another chunk
+    shard.params[1].grad[299] = float("nan")
+    # masters beyond the fp16 range round to infinity
+    p.master[10:16] = torch.tensor([65519.0, 65530.0, -70000.0, 1e-7, -3e-8, 3.4e38], device=DEV)
+    host = [wl.to_numpy_bytes(t) for t in shard.segments]
+    params_np = [(host[4 * i].view(np.uint16), host[4 * i + 1].view(np.float32),
+                  host[4 * i + 2].view(np.float32), host[4 * i + 3].view(np.float32))
+                 for i in range(2)]
+    grads_np = [wl.to_numpy_bytes(q.grad).view(np.uint16) for q in shard.params]
+    plan = ff.plan_for_shard(shard)
+    chunks, crcs, _, _ = ff.alloc_outputs(plan, DEV)
+    n_nonfinite = torch.full((1,), -1, dtype=torch.int64, device=DEV)
+    inv = float(np.float32(1.0 / 1024.0))
+    ff.ff_adam_step_snapshot_f16(plan, [q.grad for q in shard.params], HP, inv, n_nonfinite,
+                                 chunks, crcs)
+    torch.cuda.synchronize()
+    _, _, want_bad = oracle.adam_snapshot_f16(params_np, grads_np, inv, host, 4096, HP)
+    assert want_bad == 5 and int(n_nonfinite.item()) == 5
+    # NaN results: compare NaN-ness (sign and payload of a NaN result are not fixed by IEEE 754);
+    # everything else bit for bit
+    for q, (w16, master, m, v) in zip(shard.params, params_np):
+        for got_t, want in ((q.master, master), (q.m, m), (q.v, v)):
+            got = got_t.cpu().numpy()
+            nan = np.isnan(want)
+            assert np.array_equal(np.isnan(got), nan)
+            assert np.array_equal(got.view(np.uint32)[~nan], want.view(np.uint32)[~nan])
+        got_w = wl.to_numpy_bytes(q.w16).view(np.uint16)
+        nan_w = np.isnan(w16.view(np.float16))
+        assert np.array_equal(np.isnan(got_w.view(np.float16)), nan_w)
+        assert np.array_equal(got_w[~nan_w], w16[~nan_w])
+    w = wl.to_numpy_bytes(p.w16).view(np.uint16)
+    assert w[11] == 0x7C00 and w[12] == 0xFC00 and w[15] == 0x7C00     # overflow to infinity
+    assert w[10] == 0x7BFF                                             # 65519 * decay stays finite
+    # n_nonfinite may be NULL; the snapshot equals ff_pack of the state left in place
+    chunks2, crcs2, _, _ = ff.alloc_outputs(plan, DEV)
+    ff.ff_pack(plan, chunks2, crcs2)
+    torch.cuda.synchronize()
+    assert torch.equal(chunks, chunks2) and torch.equal(crcs, crcs2)
+    ff.ff_adam_step_snapshot_f16(plan, [q.grad for q in shard.params], HP, inv, None, chunks, crcs)
+    torch.cuda.synchronize()
+
+
+def test_fused_adam_format_mismatch_is_rejected():
+    bf = wl.param_shard("b", [1000], 4096, 1, DEV, with_grads=True)
+    fh = wl.param_shard("h", [1000], 4096, 1, DEV, with_grads=True, half=torch.float16)
+    for shard, wrong in ((bf, "f16"), (fh, "bf16")):
+        plan = ff.plan_for_shard(shard)
+        chunks, crcs, _, _ = ff.alloc_outputs(plan, DEV)
+        grads = [q.grad for q in shard.params]
+        with pytest.raises(ff.FFError) as e:
+            if wrong == "f16":
+                ff.ff_adam_step_snapshot_f16(plan, grads, HP, 1.0, None, chunks, crcs)
+            else:
+                ff.ff_adam_step_snapshot(plan, grads, HP, chunks, crcs)
+        assert e.value.status == ff.FF_ERR_INVALID
+    # a plan that mixes the two 16-bit formats has no valid fused step; it still packs
+    mixed = list(bf.segments) + list(fh.segments)
+    kinds = [ff.FF_KIND_W16, ff.FF_KIND_MASTER, ff.FF_KIND_M, ff.FF_KIND_V] * 2
+    plan = ff.ff_snapshot_plan(mixed, 4096, kinds=kinds, param_ids=[0] * 4 + [1] * 4)
+    assert plan.num_params == 0
+    chunks, crcs, _, _ = ff.alloc_outputs(plan, DEV)
+    ff.ff_pack(plan, chunks, crcs)
+    torch.cuda.synchronize()
 
 # ---- selective restore ------------------------------------------------------------------------------
 

@@ -114,6 +114,16 @@ def test_parameter_groups():
     p = shard.params[0]
     plan = _host_plan([p.w16, p.master, p.m], 1024, kinds=kinds, param_ids=[0, 0, 0])
     assert plan.num_params == 0 and plan.payload_bytes == 10 * 10
+    # fp16 working weights form groups as well; one plan holds one 16-bit format
+    half = wl.param_shard("h", [10, 20], 1024, 3, "cpu", half=torch.float16)
+    assert ff.plan_for_shard(half, flags=ff.FF_PLAN_HOST_ONLY).num_params == 2
+    kinds = [ff.FF_KIND_W16, ff.FF_KIND_MASTER, ff.FF_KIND_M, ff.FF_KIND_V] * 2
+    q = half.params[1]
+    both = [p.w16, p.master, p.m, p.v, q.w16, q.master, q.m, q.v]
+    assert _host_plan(both, 1024, kinds=kinds, param_ids=[0] * 4 + [1] * 4).num_params == 0
+    # an fp32 tensor in the working-weight role is not a group
+    assert _host_plan([p.master.clone(), p.master, p.m, p.v], 1024, kinds=kinds[:4],
+                      param_ids=[0] * 4).num_params == 0
 
 
 def test_fold_relations_are_multiples_of_the_generator(oracle):
