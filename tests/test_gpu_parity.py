@@ -194,6 +194,48 @@ def test_verify_only_every_tile_position(oracle, chunk, tile_log2):
             assert np.array_equal(got[lo:hi], clean[lo:hi])
 
 
+def test_empty_segments_and_exact_multiple_of_the_chunk(oracle):
+    # empty tensors take no place in the stream; a payload that is a whole number of chunks has
+    # no zero tail; a payload smaller than one chunk is one chunk, mostly zeros
+    g = torch.Generator(device=DEV)
+    g.manual_seed(11)
+    mk = lambda n, dt: torch.randn(n, device=DEV, generator=g).to(dt)
+    segs = [mk(0, torch.float32), mk(3 * 1024, torch.float32), mk(0, torch.bfloat16),
+            mk(2 * 1024, torch.bfloat16), mk(0, torch.float32)]
+    shard = wl.Shard("z", 4096, segs, [])
+    state = _pack_and_compare(shard, oracle)
+    plan = state[0]
+    assert plan.payload_bytes == 16384 == plan.buffer_bytes and plan.num_segments == 2
+    _restore_and_compare(shard, *state[:6])
+    small = wl.Shard("y", 1 << 20, [mk(5, torch.bfloat16), mk(1, torch.float32)], [])
+    state = _pack_and_compare(small, oracle)
+    plan = state[0]
+    assert plan.payload_bytes == 14 and plan.num_chunks == 1 and plan.buffer_bytes == 1 << 20
+    _restore_and_compare(small, *state[:6])
+
+
+def test_maximum_chunk_size(oracle):
+    # 1 GiB chunks: two of them, the second mostly zero tail; the fused step crosses the boundary
+    C = 1 << 30
+    numels = [60 * (1 << 20) + 3, 20 * (1 << 20) + 1]           # 80 Mi elements, 1.17 GB
+    shard, plan = _adam_and_compare(oracle, numels, C, seed=12)
+    assert plan.num_chunks == 2 and plan.chunk_bytes == C
+    chunks, crcs, bad, n_bad = ff.alloc_outputs(plan, DEV)
+    ff.ff_pack(plan, chunks, crcs)
+    saved = [t.clone() for t in shard.segments]
+    _poison_segments(shard)
+    chunks[C + 12345] ^= 4
+    ff.ff_restore(plan, chunks, crcs, bad, n_bad)
+    torch.cuda.synchronize()
+    assert int(n_bad.item()) == 1 and bad.tolist() == [0, 1]
+    chunks[C + 12345] ^= 4
+    ff.ff_restore(plan, chunks, crcs, bad, n_bad)
+    torch.cuda.synchronize()
+    assert int(n_bad.item()) == 0
+    assert all(torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+               for a, b in zip(shard.segments, saved))
+
+
 def test_device_call_argument_errors():
     a = torch.zeros(4096, dtype=torch.float32, device=DEV)
     plan = ff.ff_snapshot_plan([a], 4096)
