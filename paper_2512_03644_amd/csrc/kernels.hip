@@ -36,8 +36,11 @@ constexpr int kDepth = 8;  // rows in flight per wavefront
 // deeper queue: with no loop there is no loop-carried register to copy and no wait for all
 // outstanding loads at a loop head.
 constexpr int kWholeRows = 32;   // rows of a default (32 KiB) tile
-constexpr int kWholeDepth = 16;  // rows in flight on that path
-static_assert(kWholeRows % kNE == 0 && kWholeDepth <= kWholeRows, "whole-tile path");
+// rows requested before the first store on that path (measured: 16 is best when the stores go to
+// the chunk buffer, the whole tile when they go to the tensors)
+template <int MODE>
+constexpr int kWholeDepth = (MODE == kRestore) ? 32 : 16;
+static_assert(kWholeRows % kNE == 0, "whole-tile path");
 static_assert(kNE % kDepth == 0, "queue slots must repeat with the state rotation");
 static_assert(kNF == 4 && kRowBytes == 1024, "one 16-byte word per lane per row");
 
@@ -256,19 +259,21 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
                 return (MODE == kPack) ? load16_unaligned<kSegNT>(tp + r * kRowBytes)
                                        : load16_stream<kBufNT>(bp + r * kRowBytes);
             };
-            u32x4 w[kWholeDepth];
-            static_for<kWholeDepth>([&](auto k) { w[k] = fetch(k); });
+            constexpr int kD = kWholeDepth<MODE>;
+            static_assert(kD <= kWholeRows, "whole-tile path");
+            u32x4 w[kD];
+            static_for<kD>([&](auto k) { w[k] = fetch(k); });
             static_for<kWholeRows>([&](auto Jc) {
                 constexpr int J = Jc;
-                const u32x4 x = w[J % kWholeDepth];
+                const u32x4 x = w[J % kD];
                 if (MODE == kPack)
                     store16_stream<kBufNT>(const_cast<uint8_t*>(bp) + J * kRowBytes, x);
                 if (MODE == kRestore)
                     store16_unaligned<kSegNT>(const_cast<uint8_t*>(tp) + J * kRowBytes, x);
                 fold_word<J % kNE>(S, x);
-                if constexpr (J + kWholeDepth < kWholeRows) {
+                if constexpr (J + kD < kWholeRows) {
                     __builtin_amdgcn_sched_barrier(0);
-                    w[J % kWholeDepth] = fetch(J + kWholeDepth);
+                    w[J % kD] = fetch(J + kD);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             });
