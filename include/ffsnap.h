@@ -30,6 +30,8 @@
  *     tile, the gradient-pointer table of the fused step): two calls on the same plan must not
  *     overlap in time.  Use one plan per concurrent stream.
  *   - Segments must not overlap each other, the chunk buffer or the crc arrays.
+ *   - A plan belongs to the device that was current when it was built; device calls made with
+ *     another device current return FF_ERR_INVALID.
  */
 #ifndef FFSNAP_H
 #define FFSNAP_H

@@ -120,6 +120,10 @@ int check_device_call(const ff_plan* p)
 {
     if (!p) return FF_ERR_NULL;
     if (p->host_only) return FF_ERR_HOST_ONLY;
+    // the plan's tables live on the device that was current when it was built
+    int dev = -1;
+    FF_HIP_TRY(hipGetDevice(&dev));
+    if (dev != p->device) return FF_ERR_INVALID;
     return FF_OK;
 }
 
