@@ -14,7 +14,6 @@ algorithmic bytes per launch over its HIP-event duration against the 8 TB/s HBM 
 same shard.
 """
 import argparse
-import glob
 import hashlib
 import json
 import os
@@ -27,13 +26,17 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 
+KERNEL_SOURCES = ("kernels.hip", "kernels.hpp", "fused.hip", "fused.hpp", "fold.h", "fold_taps.h",
+                  "gf2.h", "layout.hpp")
+
+
 def kernel_source_hash():
-    """sha256 over the library's sources: identifies the kernels a counter run belongs to."""
+    """sha256 over the files that define the device code and its tile constants: identifies the
+    kernels a counter run belongs to."""
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2512_03644_amd", "csrc", "*"))):
-        if f.endswith((".hip", ".h", ".hpp", ".cpp")):
-            h.update(os.path.basename(f).encode())
-            h.update(open(f, "rb").read())
+    for name in KERNEL_SOURCES:
+        h.update(name.encode())
+        h.update(open(os.path.join(ROOT, "paper_2512_03644_amd", "csrc", name), "rb").read())
     return h.hexdigest()
 
 

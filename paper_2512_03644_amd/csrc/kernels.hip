@@ -36,11 +36,11 @@ constexpr int kDepth = 8;  // rows in flight per wavefront
 // deeper queue: with no loop there is no loop-carried register to copy and no wait for all
 // outstanding loads at a loop head.
 constexpr int kWholeRows = 32;   // rows of a default (32 KiB) tile
+constexpr int kVerifyRows = 64;  // rows of a read-only pass's grouped (64 KiB) tile
 // rows requested before the first store on that path (measured: 16 is best when the stores go to
 // the chunk buffer, the whole tile when they go to the tensors)
 template <int MODE>
 constexpr int kWholeDepth = (MODE == kRestore) ? 32 : 16;
-static_assert(kWholeRows % kNE == 0, "whole-tile path");
 static_assert(kNE % kDepth == 0, "queue slots must repeat with the state rotation");
 static_assert(kNF == 4 && kRowBytes == 1024, "one 16-byte word per lane per row");
 
@@ -247,38 +247,48 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
     uint32_t S[kNE][kNF];
     static_for<kNE>([&](auto e) { static_for<kNF>([&](auto f) { S[e][f] = 0; }); });
 
-    // Whole-tile path: all rows real, and on the tensor side inside one segment.
-    if (T.tile_rows == kWholeRows && R == kWholeRows) {
+    // Whole-tile paths: all rows real and, on the tensor side, inside one segment.
+    auto whole_tile = [&](auto rows_c, auto depth_c, const uint8_t* bp, const uint8_t* tp) {
+        constexpr int kRows = rows_c, kD = depth_c;
+        static_assert(kRows % kNE == 0 && kD <= kRows, "whole-tile path");
+        auto fetch = [&](int r) {
+            return (MODE == kPack) ? load16_unaligned<kSegNT>(tp + r * kRowBytes)
+                                   : load16_stream<kBufNT>(bp + r * kRowBytes);
+        };
+        u32x4 w[kD];
+        static_for<kD>([&](auto k) { w[k] = fetch(k); });
+        static_for<kRows>([&](auto Jc) {
+            constexpr int J = Jc;
+            const u32x4 x = w[J % kD];
+            if (MODE == kPack) store16_stream<kBufNT>(const_cast<uint8_t*>(bp) + J * kRowBytes, x);
+            if (MODE == kRestore)
+                store16_unaligned<kSegNT>(const_cast<uint8_t*>(tp) + J * kRowBytes, x);
+            fold_word<J % kNE>(S, x);
+            if constexpr (J + kD < kRows) {
+                __builtin_amdgcn_sched_barrier(0);
+                w[J % kD] = fetch(J + kD);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+        const uint32_t reg = reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]);
+        if (lane == 0) partial[tile] = reg;
+    };
+    if (R == static_cast<int>(T.tile_rows)) {
         const uint8_t* bp = chunks + s_base + lane16;  // buffer side
         const uint8_t* tp = bp;                        // tensor side
-        bool whole = true;
-        if (MODE == kPack) whole = span_in_segment(cin, s_base, kWholeRows, &tp);
-        if (MODE == kRestore) whole = span_in_segment(cout, s_base, kWholeRows, &tp);
-        if (whole) {
-            auto fetch = [&](int r) {
-                return (MODE == kPack) ? load16_unaligned<kSegNT>(tp + r * kRowBytes)
-                                       : load16_stream<kBufNT>(bp + r * kRowBytes);
-            };
-            constexpr int kD = kWholeDepth<MODE>;
-            static_assert(kD <= kWholeRows, "whole-tile path");
-            u32x4 w[kD];
-            static_for<kD>([&](auto k) { w[k] = fetch(k); });
-            static_for<kWholeRows>([&](auto Jc) {
-                constexpr int J = Jc;
-                const u32x4 x = w[J % kD];
-                if (MODE == kPack)
-                    store16_stream<kBufNT>(const_cast<uint8_t*>(bp) + J * kRowBytes, x);
-                if (MODE == kRestore)
-                    store16_unaligned<kSegNT>(const_cast<uint8_t*>(tp) + J * kRowBytes, x);
-                fold_word<J % kNE>(S, x);
-                if constexpr (J + kD < kWholeRows) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    w[J % kD] = fetch(J + kD);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            });
-            const uint32_t reg = reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]);
-            if (lane == 0) partial[tile] = reg;
+        if (T.tile_rows == kWholeRows) {
+            bool whole = true;
+            if (MODE == kPack) whole = span_in_segment(cin, s_base, kWholeRows, &tp);
+            if (MODE == kRestore) whole = span_in_segment(cout, s_base, kWholeRows, &tp);
+            if (whole) {
+                whole_tile(std::integral_constant<int, kWholeRows>{},
+                           std::integral_constant<int, kWholeDepth<MODE>>{}, bp, tp);
+                return;
+            }
+        }
+        if (MODE == kVerify && T.tile_rows == kVerifyRows) {
+            whole_tile(std::integral_constant<int, kVerifyRows>{},
+                       std::integral_constant<int, kWholeDepth<kVerify>>{}, bp, tp);
             return;
         }
     }
