@@ -348,16 +348,28 @@ int adam_impl(const ff_plan* p, const void* const* grads, const ff_adam_hparams*
     }
     c.inv_scale = inv_scale;
     c.n_nonfinite = n_nonfinite;
-    // the pointer array is copied into the plan first: the asynchronous upload reads from there
-    try {
-        p->host_grads.resize(L.params.size());
-    } catch (const std::bad_alloc&) {
-        return FF_ERR_NOMEM;
+    // The device table of gradient pointers is refreshed only when a pointer differs from the last
+    // call's (a training loop passes the same buffers every step).  The array is copied into the
+    // plan first: the asynchronous upload reads from there.
+    bool same = p->host_grads.size() == L.params.size();
+    for (size_t i = 0; same && i < L.params.size(); i++)
+        same = p->host_grads[i] == reinterpret_cast<uint64_t>(grads[i]);
+    if (!same) {
+        try {
+            p->host_grads.resize(L.params.size());
+        } catch (const std::bad_alloc&) {
+            return FF_ERR_NOMEM;
+        }
+        for (size_t i = 0; i < L.params.size(); i++)
+            p->host_grads[i] = reinterpret_cast<uint64_t>(grads[i]);
+        const hipError_t e = hipMemcpyAsync(p->grads, p->host_grads.data(),
+                                            L.params.size() * sizeof(uint64_t),
+                                            hipMemcpyHostToDevice, s);
+        if (e != hipSuccess) {
+            p->host_grads.clear();  // the device table is in an unknown state
+            return hip_fail(e);
+        }
     }
-    for (size_t i = 0; i < L.params.size(); i++)
-        p->host_grads[i] = reinterpret_cast<uint64_t>(grads[i]);
-    FF_HIP_TRY(hipMemcpyAsync(p->grads, p->host_grads.data(), L.params.size() * sizeof(uint64_t),
-                              hipMemcpyHostToDevice, s));
     FF_HIP_TRY(launch_fused(half_dtype == FF_F16, p->work, p->n_work, p->grads, p->fused_tabs,
                             chunks, crcs, L.n_chunks, L.payload, L.buffer_bytes, p->affine, c, s));
     return FF_OK;

@@ -416,6 +416,35 @@ def test_fused_adam_argument_errors():
     assert e.value.status == ff.FF_ERR_INVALID
 
 
+def test_fused_adam_consecutive_steps_and_new_gradient_buffers(oracle):
+    """Three steps on one plan: the same gradient buffers twice (their pointers are uploaded once),
+    then different buffers.  The oracle takes the same three steps."""
+    numels = [3000, 70001, 255]
+    shard = wl.param_shard("a", numels, 4096, 21, DEV, with_grads=True)
+    plan = ff.plan_for_shard(shard)
+    host = [wl.to_numpy_bytes(t) for t in shard.segments]
+    params_np = [(host[4 * i].view(np.uint16), host[4 * i + 1].view(np.float32),
+                  host[4 * i + 2].view(np.float32), host[4 * i + 3].view(np.float32))
+                 for i in range(len(numels))]
+    chunks, crcs, _, _ = ff.alloc_outputs(plan, DEV)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(77)
+    grads_a = [p.grad for p in shard.params]
+    grads_b = [torch.randn(n, device=DEV, generator=g).mul_(1e-3).to(torch.bfloat16) for n in numels]
+    for step, grads in ((1, grads_a), (2, grads_a), (3, grads_b)):
+        hp = dict(HP, step=step)
+        if step == 2:
+            for t in grads_a:                       # new values in the same buffers
+                t.copy_(torch.randn(t.numel(), device=DEV, generator=g).mul_(1e-3))
+        ff.ff_adam_step_snapshot(plan, grads, hp, chunks, crcs)
+        torch.cuda.synchronize()
+        grads_np = [wl.to_numpy_bytes(t).view(np.uint16) for t in grads]
+        want_buf, want_crcs = oracle.adam_snapshot(params_np, grads_np, host, 4096, hp)
+        assert np.array_equal(chunks.cpu().numpy(), want_buf), step
+        assert np.array_equal(_u32(crcs), want_crcs), step
+        for t, h in zip(shard.segments, host):
+            assert np.array_equal(wl.to_numpy_bytes(t), h), step
+
 
 # ---- fp16 variant of the fused step ---------------------------------------------------------------
 
