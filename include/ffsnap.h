@@ -30,6 +30,10 @@
  *     tile, the gradient-pointer table of the fused step): two calls on the same plan must not
  *     overlap in time.  Use one plan per concurrent stream.
  *   - Segments must not overlap each other, the chunk buffer or the crc arrays.
+ *   - ff_pack, ff_restore and the fused step allocate nothing and only launch kernels, so they
+ *     can be recorded into a HIP graph; the fused step copies its gradient-pointer table to the
+ *     device when a pointer differs from the previous call's, so call it once eagerly with the
+ *     same gradient buffers before capturing it.
  *   - A plan belongs to the device that was current when it was built; device calls made with
  *     another device current return FF_ERR_INVALID.
  */

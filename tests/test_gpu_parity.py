@@ -445,6 +445,50 @@ def test_fused_adam_consecutive_steps_and_new_gradient_buffers(oracle):
         for t, h in zip(shard.segments, host):
             assert np.array_equal(wl.to_numpy_bytes(t), h), step
 
+def test_hip_graph_replays_of_the_whole_step():
+    """The device entry points only launch kernels (the fused step uploads its gradient pointers
+    on the first call alone), so a step can be captured into a HIP graph.  Every replay, with
+    eager work between replays, must equal the eager result."""
+    numels = [3000, 70001, 255, 40000]
+    shard = wl.param_shard("a", numels, 1 << 16, 33, DEV, with_grads=True)
+    plan = ff.plan_for_shard(shard)
+    grads = [p.grad for p in shard.params]
+    chunks, crcs, bad, n_bad = ff.alloc_outputs(plan, DEV)
+    pk, pcrcs, _, _ = ff.alloc_outputs(plan, DEV)
+
+    def step():
+        ff.ff_adam_step_snapshot(plan, grads, HP, chunks, crcs)
+        ff.ff_pack(plan, pk, pcrcs)
+        ff.ff_restore(plan, chunks, crcs, bad, n_bad)
+
+    step()                                           # eager once: uploads the pointer table
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(5)
+    for rep in range(3):
+        start = [t.clone() for t in shard.segments]
+        for t in grads:                              # eager work between the replays
+            t.copy_(torch.randn(t.numel(), device=DEV, generator=gen).mul_(1e-3))
+        for out in (chunks, pk):
+            out.fill_(0xA5)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in shard.segments] + [chunks.clone(), crcs.clone(), pk.clone(),
+                                                     pcrcs.clone(), bad.clone(), n_bad.clone()]
+        for t, s0 in zip(shard.segments, start):
+            t.copy_(s0)
+        for out in (chunks, pk):
+            out.fill_(0xA5)
+        step()
+        torch.cuda.synchronize()
+        want = list(shard.segments) + [chunks, crcs, pk, pcrcs, bad, n_bad]
+        for a, b in zip(got, want):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), rep
+        assert int(n_bad.item()) == 0 and torch.equal(chunks, pk) and torch.equal(crcs, pcrcs)
+
 
 # ---- fp16 variant of the fused step ---------------------------------------------------------------
 
