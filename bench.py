@@ -191,7 +191,8 @@ def main():
     for name, fn, nbytes in ops:
         ts = [a.elapsed_time(b) for a, b in evs[name]]
         avg = sum(ts) / len(ts)
-        detail[name] = {"avg_ms": round(avg, 4), "min_ms": round(min(ts), 4),
+        detail[name] = {"avg_ms": round(avg, 4), "median_ms": round(sorted(ts)[len(ts) // 2], 4),
+                        "min_ms": round(min(ts), 4),
                         "traffic_GBps": round(nbytes / avg / 1e6, 1),
                         "frac_of_peak": round(nbytes / avg / 1e6 / HBM_PEAK_GBS, 4)}
     detail["pack"]["payload_GBps"] = round(N / detail["pack"]["avg_ms"] / 1e6, 1)
@@ -201,6 +202,8 @@ def main():
     ts = event_ms(lambda: ff.ff_copy_ceiling(chunks, src, N), 5, torch)
     copy_gbs = 2 * N / (sum(ts) / len(ts)) / 1e6
     del src
+    for name in detail:
+        detail[name]["frac_of_copy_ceiling"] = round(detail[name]["traffic_GBps"] / copy_gbs, 4)
 
     # roofline of the dominant (longest-running) kernel of the step
     kernels = {"adam_snapshot": ("fused_kernel", 42 * n_el), "pack": ("tile_kernel<pack>", 2 * N),
