@@ -291,6 +291,114 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
                        std::integral_constant<int, kWholeDepth<kVerify>>{}, bp, tp);
             return;
         }
+        // Piecewise path: a default-size tile that starts inside the payload and touches at most
+        // kPieces segments; the end of the payload counts as one more boundary, behind which
+        // lanes read zeros (pack) or store nothing (restore).  Every lane picks the segment of
+        // its own 16 bytes by comparing its offset in the tile with the (wave-uniform) segment
+        // boundaries, so a row that contains a boundary is still one vector access with per-lane
+        // addresses and the code stays straight-line.  Only lanes whose 16 bytes straddle a
+        // boundary cannot be served that way: they read a harmless address instead (their own
+        // slot of the buffer row) and then move their 8 halfwords one by one, each located by
+        // the same comparisons.
+        if (MODE != kVerify && T.tile_rows == kWholeRows && s_base < T.payload) {
+            constexpr int kPieces = 4;
+            const uint32_t first = tile_first_seg[tile];
+            uint64_t a[kPieces + 1];
+            static_for<kPieces + 1>([&](auto k) {
+                const uint32_t i = first + k < T.n_seg ? first + k : T.n_seg;
+                a[k] = seg_off[i];  // seg_off[n_seg] is the payload size
+            });
+            if (a[kPieces] >= s_base + uint64_t(kWholeRows) * kRowBytes || a[kPieces] >= T.payload) {
+                constexpr uint32_t kTileBytes = kWholeRows * kRowBytes;
+                const uint64_t left = T.payload - s_base;  // payload bytes from the tile start on
+                const uint32_t pend = left < kTileBytes ? static_cast<uint32_t>(left) : kTileBytes;
+                uint32_t rb[kPieces - 1];  // boundaries relative to the tile (>= kTileBytes: none)
+                uint64_t base[kPieces];    // address of tile offset 0 if it lay in segment k
+                static_for<kPieces>([&](auto k) {
+                    const uint32_t i = first + k < T.n_seg ? first + k : T.n_seg - 1;
+                    base[k] = seg_ptr[i] + (s_base - a[k]);  // modulo 2^64 for k >= 1
+                });
+                static_for<kPieces - 1>([&](auto k) {
+                    const uint64_t d = a[k + 1] - s_base;  // a[k + 1] > s_base
+                    rb[k] = d < kTileBytes ? static_cast<uint32_t>(d) : kTileBytes;
+                });
+                // per-lane address of the lane's 16 bytes of row J on the tensor side, whether
+                // they straddle a boundary, and whether they lie wholly behind the payload
+                auto locate = [&](int J, bool& straddle, bool& beyond) -> const uint8_t* {
+                    const uint32_t rel = static_cast<uint32_t>(J) * kRowBytes + lane16;
+                    uint64_t b = base[0];
+                    beyond = rel >= pend;
+                    straddle = !beyond && rel + 16u > pend;
+                    static_for<kPieces - 1>([&](auto k) {
+                        const bool past = rel >= rb[k];
+                        b = past ? base[k + 1] : b;
+                        straddle = straddle || (!past && rel + 16u > rb[k]);
+                    });
+                    return reinterpret_cast<const uint8_t*>(b + rel);
+                };
+                // address of the halfword at tile offset rel2 (a halfword never straddles)
+                auto locate_half = [&](uint32_t rel2) -> uint64_t {
+                    uint64_t b = base[0];
+                    static_for<kPieces - 1>([&](auto k) { b = rel2 >= rb[k] ? base[k + 1] : b; });
+                    return b + rel2;
+                };
+                constexpr int kD = kWholeDepth<kPack>;
+                auto fetch = [&](int J) -> u32x4 {
+                    if (MODE == kRestore) return load16_stream<kBufNT>(bp + J * kRowBytes);
+                    bool straddle, beyond;
+                    const uint8_t* p = locate(J, straddle, beyond);
+                    if (straddle || beyond) p = bp + J * kRowBytes;  // a valid address: value unused
+                    return load16_unaligned<kSegNT>(p);
+                };
+                u32x4 w[kD];
+                static_for<kD>([&](auto k) { w[k] = fetch(k); });
+                static_for<kWholeRows>([&](auto Jc) {
+                    constexpr int J = Jc;
+                    u32x4 x = w[J % kD];
+                    bool straddle, beyond;
+                    const uint8_t* p = locate(J, straddle, beyond);
+                    const uint32_t rel = static_cast<uint32_t>(J) * kRowBytes + lane16;
+                    if (MODE == kPack) {
+                        if (beyond) x = u32x4{0, 0, 0, 0};
+                        if (straddle) {  // halfword by halfword, zeros behind the payload
+                            uint32_t h[8];
+#pragma unroll
+                            for (int u = 0; u < 8; u++) {
+                                const uint32_t rel2 = rel + 2u * u;
+                                h[u] = 0;
+                                if (rel2 < pend)
+                                    h[u] = *as_global(reinterpret_cast<const uint16_t*>(locate_half(rel2)));
+                            }
+                            x = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16),
+                                      h[6] | (h[7] << 16)};
+                        }
+                        store16_stream<kBufNT>(const_cast<uint8_t*>(bp) + J * kRowBytes, x);
+                    } else {
+                        if (straddle) {
+                            const uint32_t d[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+                            for (int u = 0; u < 8; u++) {
+                                const uint32_t rel2 = rel + 2u * u;
+                                if (rel2 < pend)
+                                    *as_global(reinterpret_cast<uint16_t*>(locate_half(rel2))) =
+                                        static_cast<uint16_t>(d[u >> 1] >> ((u & 1) * 16));
+                            }
+                        } else if (!beyond) {
+                            store16_unaligned<kSegNT>(const_cast<uint8_t*>(p), x);
+                        }
+                    }
+                    fold_word<J % kNE>(S, x);
+                    if constexpr (J + kD < kWholeRows) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        w[J % kD] = fetch(J + kD);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                });
+                const uint32_t reg = reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]);
+                if (lane == 0) partial[tile] = reg;
+                return;
+            }
+        }
     }
 
     // queue slot of row r is (r + pad) mod kDepth; fill the first kDepth rows
