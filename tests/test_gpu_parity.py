@@ -108,6 +108,44 @@ def test_ragged_unaligned_segments(oracle, seed, mu, n):
     _restore_and_compare(shard, *state[:6])
 
 
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_tiles_with_a_few_segment_boundaries(oracle, seed):
+    # tensors of 4-40 KB at every 2-byte misalignment: most 32 KiB tiles hold 2-5 pieces
+    lay = wl.fragmented_layout(seed=seed, n_tensors=1200, mu=8.6, sigma=0.6, max_numel=1 << 15)
+    shard = wl.fragmented_shard(lay, 1 << 17, seed=seed, device=DEV)
+    state = _pack_and_compare(shard, oracle)
+    _restore_and_compare(shard, *state[:6])
+
+
+@pytest.mark.parametrize("tail", [2, 14, 16, 18, 1022, 1024, 1026, 16384 + 6, 32766])
+def test_payload_end_inside_a_tile(oracle, tail):
+    # three full tiles, then `tail` bytes split over segments of 2-byte granularity: the payload
+    # ends inside the fourth tile at every kind of position (inside a lane, on a lane or row edge)
+    lay = [(3 * 16384 + 5, 2, 2), (max(tail // 2 - 5, 0), 2, 6)]
+    if tail // 2 - 5 < 0:
+        lay = [(3 * 16384 + tail // 2, 2, 2)]
+    shard = wl.fragmented_shard(lay, 1 << 17, seed=tail, device=DEV)
+    assert shard.payload_bytes == 3 * 32768 + tail
+    state = _pack_and_compare(shard, oracle)
+    _restore_and_compare(shard, *state[:6])
+
+
+@pytest.mark.parametrize("pieces", [2, 3, 4, 5, 6])
+def test_boundaries_at_every_offset_in_a_lane(oracle, pieces):
+    # one 32 KiB tile cut into `pieces` segments; the cuts walk through all eight halfword
+    # positions of a lane, include segments shorter than a lane, and two cuts inside one lane
+    lay, used = [], 0
+    cuts = [1024 * 3 + 2 * k for k in range(8)][:pieces - 1]
+    cuts = sorted(set(cuts + ([9000, 9002, 9006] if pieces >= 4 else [])))[:pieces - 1]
+    for c in cuts + [32768]:
+        lay.append(((c - used) // 2, 2, (2 * len(lay)) % 16))
+        used = c
+    lay.append((20000, 4, 4))                       # more tiles behind it
+    shard = wl.fragmented_shard(lay, 1 << 16, seed=pieces, device=DEV)
+    state = _pack_and_compare(shard, oracle)
+    _restore_and_compare(shard, *state[:6])
+
+
 def test_single_element_segments(oracle):
     lay = [(1, 2, (2 * i) % 16) for i in range(3000)] + [(1, 4, (4 * i) % 16) for i in range(500)]
     shard = wl.fragmented_shard(lay, 1024, seed=9, device=DEV)
