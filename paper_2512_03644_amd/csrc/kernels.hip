@@ -503,34 +503,59 @@ __device__ __forceinline__ uint32_t chunk_register(const uint32_t* __restrict__ 
     return gf2_mul_const<kX32>(acc);  // the tiles' registers are stored without their factor x^32
 }
 
-__global__ void combine_pack_kernel(const uint32_t* __restrict__ partial, uint32_t tiles_per_chunk,
-                                    uint32_t x_tile, uint32_t affine, uint64_t n_chunks,
-                                    uint32_t* __restrict__ crcs)
+// The same by one wavefront (result in lane 0; n a power of two): lane l folds its own run of
+// m = max(n / 64, 1) consecutive registers, then neighbouring runs are merged pairwise, the left
+// one multiplied by x_tile^(registers in the right one).
+__device__ __forceinline__ uint32_t chunk_register_wave(const uint32_t* __restrict__ partial,
+                                                        uint64_t first, uint32_t n,
+                                                        uint32_t x_tile, uint32_t lane)
 {
-    const uint64_t j = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (j >= n_chunks) return;
-    crcs[j] = chunk_register(partial, j * tiles_per_chunk, tiles_per_chunk, x_tile) ^ affine;
+    const uint32_t lanes = n < kWaveSize ? n : kWaveSize;
+    const uint32_t m = n / lanes;
+    uint32_t acc = 0;
+    if (lane < lanes)
+        for (uint32_t j = 0; j < m; j++)
+            acc = gf2_mul(acc, x_tile) ^ partial[first + uint64_t(lane) * m + j];
+    uint32_t xp = x_tile;  // x_tile^m, then squared level by level
+    for (uint32_t k = 1; k < m; k <<= 1) xp = gf2_mul(xp, xp);
+    for (uint32_t d = 1; d < lanes; d <<= 1) {
+        const uint32_t right = __shfl_down(acc, d);
+        if ((lane & (2 * d - 1)) == 0) acc = gf2_mul(acc, xp) ^ right;
+        xp = gf2_mul(xp, xp);
+    }
+    return gf2_mul_const<kX32>(acc);
 }
 
-__global__ void combine_verify_kernel(const uint32_t* __restrict__ partial,
-                                      uint32_t tiles_per_chunk, uint32_t x_tile, uint32_t affine,
-                                      uint64_t n_chunks, const uint32_t* __restrict__ chunk_list,
-                                      const uint32_t* __restrict__ crcs,
-                                      uint32_t* __restrict__ bad, uint64_t* __restrict__ n_bad)
+constexpr int kCombineWaves = 4;  // chunks per workgroup of the combine kernels
+
+__global__ __launch_bounds__(kWaveSize* kCombineWaves) void combine_pack_kernel(
+    const uint32_t* __restrict__ partial, uint32_t tiles_per_chunk, uint32_t x_tile,
+    uint32_t affine, uint64_t n_chunks, uint32_t* __restrict__ crcs)
 {
-    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-    bool is_bad = false;
-    if (i < n_chunks) {
-        const uint64_t j = chunk_list ? chunk_list[i] : i;
-        const uint32_t crc =
-            chunk_register(partial, j * tiles_per_chunk, tiles_per_chunk, x_tile) ^ affine;
-        is_bad = (crc != crcs[j]);
+    const uint32_t lane = threadIdx.x & (kWaveSize - 1);
+    const uint64_t j = static_cast<uint64_t>(blockIdx.x) * kCombineWaves + threadIdx.x / kWaveSize;
+    if (j >= n_chunks) return;
+    const uint32_t reg =
+        chunk_register_wave(partial, j * tiles_per_chunk, tiles_per_chunk, x_tile, lane);
+    if (lane == 0) crcs[j] = reg ^ affine;
+}
+
+__global__ __launch_bounds__(kWaveSize* kCombineWaves) void combine_verify_kernel(
+    const uint32_t* __restrict__ partial, uint32_t tiles_per_chunk, uint32_t x_tile,
+    uint32_t affine, uint64_t n_chunks, const uint32_t* __restrict__ chunk_list,
+    const uint32_t* __restrict__ crcs, uint32_t* __restrict__ bad, uint64_t* __restrict__ n_bad)
+{
+    const uint32_t lane = threadIdx.x & (kWaveSize - 1);
+    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * kCombineWaves + threadIdx.x / kWaveSize;
+    if (i >= n_chunks) return;
+    const uint64_t j = chunk_list ? chunk_list[i] : i;
+    const uint32_t reg =
+        chunk_register_wave(partial, j * tiles_per_chunk, tiles_per_chunk, x_tile, lane);
+    if (lane == 0) {
+        const bool is_bad = (reg ^ affine) != crcs[j];
         bad[j] = is_bad ? 1u : 0u;
+        if (is_bad) atomicAdd(reinterpret_cast<unsigned long long*>(n_bad), 1ull);
     }
-    const uint64_t votes = __ballot(is_bad);
-    if ((threadIdx.x & (kWaveSize - 1)) == 0 && votes)
-        atomicAdd(reinterpret_cast<unsigned long long*>(n_bad),
-                  static_cast<unsigned long long>(__popcll(votes)));
 }
 
 __global__ void finish_crc_kernel(const uint32_t* __restrict__ partial, uint32_t n_tiles,
@@ -605,8 +630,8 @@ hipError_t launch_combine_pack(const uint32_t* partial, uint32_t tiles_per_chunk
                                uint32_t affine, uint64_t n_chunks, uint32_t* crcs,
                                hipStream_t stream)
 {
-    const unsigned block = 256;
-    const unsigned grid = static_cast<unsigned>((n_chunks + block - 1) / block);
+    const unsigned block = kWaveSize * kCombineWaves;  // one wavefront per chunk
+    const unsigned grid = static_cast<unsigned>((n_chunks + kCombineWaves - 1) / kCombineWaves);
     hipLaunchKernelGGL(combine_pack_kernel, dim3(grid), dim3(block), 0, stream, partial,
                        tiles_per_chunk, x_tile, affine, n_chunks, crcs);
     return hipGetLastError();
@@ -618,8 +643,8 @@ hipError_t launch_combine_verify(const uint32_t* partial, uint32_t tiles_per_chu
                                  uint64_t* n_bad, hipStream_t stream)
 {
     if (n_chunks == 0) return hipSuccess;
-    const unsigned block = 256;
-    const unsigned grid = static_cast<unsigned>((n_chunks + block - 1) / block);
+    const unsigned block = kWaveSize * kCombineWaves;  // one wavefront per chunk
+    const unsigned grid = static_cast<unsigned>((n_chunks + kCombineWaves - 1) / kCombineWaves);
     hipLaunchKernelGGL(combine_verify_kernel, dim3(grid), dim3(block), 0, stream, partial,
                        tiles_per_chunk, x_tile, affine, n_chunks, chunk_list, crcs, bad, n_bad);
     return hipGetLastError();
