@@ -11,8 +11,8 @@
 // elements are zeros that do not change a CRC register started from 0.  At the end of the tile
 // each stream's state is reduced to a register, multiplied by x^(8 * distance to the end of its
 // chunk) and XORed into crcs[chunk] with an atomic; XOR is commutative, so the result does not
-// depend on the order in which tiles finish.  A prepare kernel zeroes crcs[] and the zero tail
-// of the last chunk; a finish kernel adds the preset/complement term.
+// depend on the order in which tiles finish.  A prepare kernel sets crcs[] to the preset/complement
+// term and writes the zero tail of the last chunk.
 #include "fused.hpp"
 
 #include <hip/hip_fp16.h>
@@ -435,24 +435,19 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
     }
 }
 
-// crcs[] = 0, the tail of the last chunk = 0, and the non-finite gradient counter = 0
-__global__ void fused_prepare_kernel(uint32_t* __restrict__ crcs, uint64_t n_chunks,
+// crcs[] = the preset/complement term (the tiles XOR their pieces into it), the tail of the last
+// chunk = 0, and the non-finite gradient counter = 0
+__global__ void fused_prepare_kernel(uint32_t* __restrict__ crcs, uint64_t n_chunks, uint32_t affine,
                                      uint8_t* __restrict__ chunks, uint64_t payload,
                                      uint64_t buffer_bytes, uint64_t* __restrict__ n_nonfinite)
 {
     const uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i == 0 && n_nonfinite) *n_nonfinite = 0;
     const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
-    for (uint64_t j = i; j < n_chunks; j += stride) crcs[j] = 0;
+    for (uint64_t j = i; j < n_chunks; j += stride) crcs[j] = affine;
     uint16_t* tail = reinterpret_cast<uint16_t*>(chunks + payload);  // payload is even
     const uint64_t n_half = (buffer_bytes - payload) / 2;
     for (uint64_t j = i; j < n_half; j += stride) tail[j] = 0;
-}
-
-__global__ void fused_finish_kernel(uint32_t* __restrict__ crcs, uint64_t n_chunks, uint32_t affine)
-{
-    const uint64_t j = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (j < n_chunks) crcs[j] ^= affine;
 }
 
 }  // namespace
@@ -481,7 +476,7 @@ hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_tiles, const
     if (prep_blocks == 0) prep_blocks = 1;
     if (prep_blocks > 4096) prep_blocks = 4096;
     hipLaunchKernelGGL(fused_prepare_kernel, dim3(prep_blocks), dim3(256), 0, stream, crcs, n_chunks,
-                       c, payload, buffer_bytes, f16 ? consts.n_nonfinite : nullptr);
+                       affine, c, payload, buffer_bytes, f16 ? consts.n_nonfinite : nullptr);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (n_tiles) {
@@ -493,11 +488,8 @@ hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_tiles, const
             hipLaunchKernelGGL(fused_kernel<false>, dim3(grid), dim3(kWaveSize * kWavesPerBlock), 0,
                                stream, tiles, n_tiles, grads, tabs, c, crcs, consts);
         e = hipGetLastError();
-        if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(fused_finish_kernel, dim3(static_cast<unsigned>((n_chunks + 255) / 256)),
-                       dim3(256), 0, stream, crcs, n_chunks, affine);
-    return hipGetLastError();
+    return e;
 }
 
 }  // namespace ffsnap

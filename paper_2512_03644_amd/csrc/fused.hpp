@@ -24,7 +24,7 @@ struct FusedConsts {
 constexpr int kFusedTabWords = 2048 + 128;
 void build_fused_tabs(uint32_t* tab);
 
-// Enqueues prepare (crcs = 0, zero tail), the tile kernel and finish (crcs ^= affine).
+// Enqueues prepare (crcs = affine, zero tail, counter = 0) and the tile kernel.
 // tiles/grads/tabs: device tables (tabs = tables for 1024-byte rows, then for 512-byte rows).
 // f16: gradients and working weights are fp16 (else bf16).
 hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_tiles, const uint64_t* grads,
