@@ -200,3 +200,42 @@ def test_checkpoint_razor_rules_and_size_law(oracle):
     ok_cfg = ff.ff_razor_config(2, 1)
     assert L.ff_razor_select(segs, 13, ctypes.byref(ok_cfg), 2, out, ctypes.byref(n)) == ff.FF_ERR_INVALID
     assert L.ff_razor_select(segs, 13, None, 0, out, ctypes.byref(n)) == ff.FF_ERR_NULL
+
+
+def test_random_layouts_agree_with_the_definition(oracle):
+    """Property check over random segment lists: sizes follow the definition, segment ranges tile
+    the stream, and every chunk's span names exactly the segments that intersect it."""
+    from hypothesis import given, settings, strategies as st
+
+    seg = st.tuples(st.integers(0, 5000), st.sampled_from([torch.bfloat16, torch.float16, torch.float32]))
+
+    @settings(max_examples=60, deadline=None)
+    @given(st.lists(seg, min_size=1, max_size=25), st.sampled_from([1024, 2048, 8192, 1 << 16]))
+    def check(segs, chunk):
+        tensors = [torch.zeros(n, dtype=dt) for n, dt in segs]
+        sizes = [t.numel() * t.element_size() for t in tensors]
+        total = sum(sizes)
+        if total == 0:
+            with pytest.raises(ff.FFError) as e:
+                _host_plan(tensors, chunk)
+            assert e.value.status == ff.FF_ERR_EMPTY
+            return
+        plan = _host_plan(tensors, chunk)
+        assert plan.payload_bytes == total
+        assert plan.num_chunks == -(-total // chunk) == oracle.num_chunks(
+            [wl.numpy_alias(t) for t in tensors], chunk)
+        assert plan.buffer_bytes == plan.num_chunks * chunk
+        nonempty = [s for s in sizes if s]
+        assert plan.num_segments == len(nonempty)
+        ranges, off = [], 0
+        for i, s in enumerate(nonempty):
+            assert plan.segment_range(i) == (off, off + s)
+            ranges.append((off, off + s))
+            off += s
+        for j in range(plan.num_chunks):
+            first, n, begin, end = plan.chunk_span(j)
+            assert (begin, end) == (j * chunk, min((j + 1) * chunk, total))
+            want = [i for i, (a, b) in enumerate(ranges) if a < end and b > begin]
+            assert list(range(first, first + n)) == want
+
+    check()
