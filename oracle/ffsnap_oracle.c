@@ -20,14 +20,16 @@
  *   adam       : one AdamW step in fp32 with a fixed operation order (below), in place,
  *                followed by pack of the updated state
  *
- * The paper fixes none of chunking, checksum or optimizer arithmetic; the readings taken are
- * listed in the design doc.  CRC32C is the Castagnoli CRC of iSCSI (RFC 3720 section 12.1):
+ * The paper fixes none of chunking, checksum or optimizer arithmetic; the definitions above
+ * are the readings taken.  CRC32C is the Castagnoli CRC of iSCSI (RFC 3720 section 12.1):
  * polynomial 0x1EDC6F41, reflected in and out, initial value and final XOR 0xFFFFFFFF.
  *
  * Parity pins (tests/test_oracle_*.py): RFC 3720 B.4 vectors and the "123456789" check value;
  * polynomial long division over GF(2) with Python integers; combine identity by brute force;
  * numpy.concatenate for pack; round trip for restore; torch.optim.AdamW in float64 and closed
- * -form special cases for Adam; torch's bf16 cast for the rounding.  Nothing here is unpinned.
+ * -form special cases for Adam; torch's bf16 cast for the rounding; numpy's IEEE conversions
+ * for the fp16 variant, and bit equality with the bf16 step on shared values.  Nothing here is
+ * unpinned.
  */
 #include <math.h>
 #include <stddef.h>
