@@ -528,6 +528,44 @@ def test_hip_graph_replays_of_the_whole_step():
         assert int(n_bad.item()) == 0 and torch.equal(chunks, pk) and torch.equal(crcs, pcrcs)
 
 
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_fused_adam_random_cases(oracle, seed):
+    """Seeded random shapes: group sizes from one element to a few tiles, any chunk size, RAW
+    tensors of both widths sprinkled between the groups, either 16-bit format."""
+    rng = np.random.default_rng(1000 + seed)
+    n_groups = int(rng.integers(1, 10))
+    numels = [int(rng.choice([rng.integers(1, 600), rng.integers(600, 9000), rng.integers(9000, 60000)]))
+              for _ in range(n_groups)]
+    chunk = int(rng.choice([1024, 2048, 16384, 65536, 1 << 18]))
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    extra = []
+    for _ in range(int(rng.integers(0, 4))):
+        n = int(rng.integers(1, 5000))
+        dt = torch.float32 if rng.random() < 0.5 else torch.bfloat16
+        pos = int(rng.integers(0, 4 * n_groups + 1)) // 4 * 4        # between two groups
+        extra.append((pos, torch.randn(n, device=DEV, generator=g).to(dt)))
+    extra.sort(key=lambda e: -e[0])                                  # insert from the back
+    half = torch.float16 if seed % 2 else torch.bfloat16
+    hp = dict(lr=float(rng.choice([1e-4, 3e-3])), beta1=0.9, beta2=float(rng.choice([0.95, 0.999])),
+              eps=1e-8, weight_decay=float(rng.choice([0.0, 0.1])), step=int(rng.integers(1, 2000)))
+    _adam_and_compare(oracle, numels, chunk, seed=2000 + seed, hp=hp, extra_raw=extra or None,
+                      half=half, loss_scale=1024.0 if seed % 2 else 1.0)
+
+
+@pytest.mark.parametrize("seed", list(range(8)))
+def test_pack_restore_random_layouts_and_tiles(oracle, seed):
+    rng = np.random.default_rng(3000 + seed)
+    mu = float(rng.uniform(4.0, 10.0))
+    lay = wl.fragmented_layout(seed=3000 + seed, n_tensors=int(rng.integers(20, 800)), mu=mu,
+                               sigma=float(rng.uniform(0.5, 2.5)), max_numel=1 << 17)
+    chunk = int(rng.choice([1024, 8192, 1 << 15, 1 << 16, 1 << 19]))
+    tile_log2 = int(rng.choice([0, 0, 10, 12, 14, 16]))
+    shard = wl.fragmented_shard(lay, chunk, seed=seed, device=DEV)
+    state = _pack_and_compare(shard, oracle, tile_log2)
+    _restore_and_compare(shard, *state[:6])
+
+
 # ---- fp16 variant of the fused step ---------------------------------------------------------------
 
 @pytest.mark.parametrize("chunk,loss_scale", [(1024, 1.0), (4096, 1024.0), (1 << 16, 65536.0),
