@@ -148,6 +148,13 @@ __device__ __forceinline__ TileGeom tile_geom(const WorkTile& t)
 }
 
 // Update wavefront `u` (0..3): rows u - pad_rows, u - pad_rows + 4, ...
+//
+// Only the first of these rows can be virtual or partial; it is handled before the loop.  From
+// then on every row is full, so the loop has no branch around a memory access: its loads are
+// unconditional and refill, in place, the register set whose values were just taken out (two sets,
+// for even and odd batches).  Registers that are never copied while a load into them is in flight,
+// and no branch between issue and use, let the compiler wait for exactly the loads a row needs,
+// while the loads of the next batch and the stores of the last one stay in flight.
 template <bool F16>
 __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G,
                                             const uint8_t* __restrict__ grad,
@@ -165,134 +172,186 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
     uint8_t* const sm = chunks + t.soff[2];
     uint8_t* const sv = chunks + t.soff[3];
     const int head_lane = G.pad_el / 4, head_sub = G.pad_el % 4;  // where element 0 sits in row 0
+    uint32_t nonfinite = 0;  // this lane's count of infinite or NaN gradient elements (fp16 only)
 
     // A row can use vector accesses if every lane holds 4 real elements.
     auto full_row = [&](int r) { return r > 0 || (r == 0 && G.pad_el == 0); };
-    // Vector loads of row r if it is a full row of the tile (nothing is requested otherwise).
-    auto load_row = [&](int r, RowIn& in) {
-        if (full_row(r) && r < G.rows) {
-            const int j0 = r * kRowElems + 4 * lane - G.pad_el;
-            in.g = load8_unaligned<true>(tg + 2 * j0);
-            in.p = load16_unaligned<true>(tp + 4 * j0);
-            in.m = load16_unaligned<true>(tm + 4 * j0);
-            in.v = load16_unaligned<true>(tv + 4 * j0);
-        }
+    auto load_row = [&](int r, RowIn& in) {  // r must be a full row of the tile
+        const int j0 = r * kRowElems + 4 * lane - G.pad_el;
+        in.g = load8_unaligned<true>(tg + 2 * j0);
+        in.p = load16_unaligned<true>(tp + 4 * j0);
+        in.m = load16_unaligned<true>(tm + 4 * j0);
+        in.v = load16_unaligned<true>(tv + 4 * j0);
     };
 
-    uint32_t nonfinite = 0;  // this lane's count of infinite or NaN gradient elements (fp16 only)
-    RowIn q0, q1;  // inputs of this wavefront's next two rows
-    q0 = q1 = RowIn{u32x2{0, 0}, u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}};
-    load_row(u - G.pad_rows, q0);
-    load_row(u - G.pad_rows + kBatchRows, q1);
-
-    for (int b = 0; b <= G.n_batches; b++) {
-        if (b < G.n_batches) {
-            const int r = b * kBatchRows + u - G.pad_rows;
-            Batch& out = buf[b & 1];
-            uint32_t fw[2] = {0, 0}, fp[4] = {0, 0, 0, 0}, fm[4] = {0, 0, 0, 0}, fv[4] = {0, 0, 0, 0};
-            const RowIn cur = q0;
-            q0 = q1;
-            load_row(r + 2 * kBatchRows, q1);
-            if (r >= 0) {
-                const int j0 = r * kRowElems + 4 * lane - G.pad_el;  // first element of the lane
-                uint32_t gb[4], wb[4];
-                float p[4], m[4], v[4];
-                if (full_row(r)) {
-                    gb[0] = cur.g.x & 0xFFFFu; gb[1] = cur.g.x >> 16;
-                    gb[2] = cur.g.y & 0xFFFFu; gb[3] = cur.g.y >> 16;
-                    p[0] = bits_to_f32(cur.p.x); p[1] = bits_to_f32(cur.p.y);
-                    p[2] = bits_to_f32(cur.p.z); p[3] = bits_to_f32(cur.p.w);
-                    m[0] = bits_to_f32(cur.m.x); m[1] = bits_to_f32(cur.m.y);
-                    m[2] = bits_to_f32(cur.m.z); m[3] = bits_to_f32(cur.m.w);
-                    v[0] = bits_to_f32(cur.v.x); v[1] = bits_to_f32(cur.v.y);
-                    v[2] = bits_to_f32(cur.v.z); v[3] = bits_to_f32(cur.v.w);
+    // copy of a row's results for the folding wavefronts
+    auto publish = [&](Batch& out, int r, uint32_t (&fw)[2], uint32_t (&fp)[4], uint32_t (&fm)[4],
+                       uint32_t (&fv)[4]) {
+        // split first element: its first two bytes close the previous chunk and must not enter
+        // this tile's CRC of that stream
+        if (r == 0 && t.head_split && lane == head_lane) {
+            uint32_t* const fx[3] = {fp, fm, fv};
+#pragma unroll
+            for (int x = 1; x <= 3; x++) {
+                if (t.head_split & (1u << x)) {
 #pragma unroll
                     for (int s = 0; s < 4; s++) {
-                        if constexpr (F16) nonfinite += f16_nonfinite(gb[s]) ? 1u : 0u;
-                        adam_element<F16>(C, gb[s], p[s], m[s], v[s], wb[s]);
-                    }
-                    const u32x2 w2 = {wb[0] | (wb[1] << 16), wb[2] | (wb[3] << 16)};
-                    const u32x4 po = {f32_to_bits(p[0]), f32_to_bits(p[1]), f32_to_bits(p[2]), f32_to_bits(p[3])};
-                    const u32x4 mo = {f32_to_bits(m[0]), f32_to_bits(m[1]), f32_to_bits(m[2]), f32_to_bits(m[3])};
-                    const u32x4 vo = {f32_to_bits(v[0]), f32_to_bits(v[1]), f32_to_bits(v[2]), f32_to_bits(v[3])};
-                    store8_unaligned<true>(tw + 2 * j0, w2);
-                    store16_unaligned<true>(tp + 4 * j0, po);
-                    store16_unaligned<true>(tm + 4 * j0, mo);
-                    store16_unaligned<true>(tv + 4 * j0, vo);
-                    store8_unaligned<true>(sw + 2 * j0, w2);
-                    store16_unaligned<true>(sp + 4 * j0, po);
-                    store16_unaligned<true>(sm + 4 * j0, mo);
-                    store16_unaligned<true>(sv + 4 * j0, vo);
-                } else {
-                    // partial first row: element by element; absent elements stay zero
-#pragma unroll
-                    for (int s = 0; s < 4; s++) {
-                        const int j = j0 + s;
-                        gb[s] = 0; wb[s] = 0; p[s] = 0.f; m[s] = 0.f; v[s] = 0.f;
-                        if (j >= 0) {
-                            gb[s] = *as_global(reinterpret_cast<const uint16_t*>(tg + 2 * j));
-                            p[s] = *as_global(reinterpret_cast<const float*>(tp + 4 * j));
-                            m[s] = *as_global(reinterpret_cast<const float*>(tm + 4 * j));
-                            v[s] = *as_global(reinterpret_cast<const float*>(tv + 4 * j));
-                            if constexpr (F16) nonfinite += f16_nonfinite(gb[s]) ? 1u : 0u;
-                            adam_element<F16>(C, gb[s], p[s], m[s], v[s], wb[s]);
-                            *as_global(reinterpret_cast<uint16_t*>(tw + 2 * j)) = static_cast<uint16_t>(wb[s]);
-                            *as_global(reinterpret_cast<float*>(tp + 4 * j)) = p[s];
-                            *as_global(reinterpret_cast<float*>(tm + 4 * j)) = m[s];
-                            *as_global(reinterpret_cast<float*>(tv + 4 * j)) = v[s];
-                            *as_global(reinterpret_cast<uint16_t*>(sw + 2 * j)) = static_cast<uint16_t>(wb[s]);
-                            // stream offsets of fp32 segments may be 2 mod 4: halfword stores
-                            const uint32_t pb = f32_to_bits(p[s]), mb = f32_to_bits(m[s]),
-                                           vb = f32_to_bits(v[s]);
-                            uint16_t* qp = reinterpret_cast<uint16_t*>(sp + 4 * j);
-                            uint16_t* qm = reinterpret_cast<uint16_t*>(sm + 4 * j);
-                            uint16_t* qv = reinterpret_cast<uint16_t*>(sv + 4 * j);
-                            *as_global(qp) = static_cast<uint16_t>(pb);
-                            *as_global(qp + 1) = static_cast<uint16_t>(pb >> 16);
-                            *as_global(qm) = static_cast<uint16_t>(mb);
-                            *as_global(qm + 1) = static_cast<uint16_t>(mb >> 16);
-                            *as_global(qv) = static_cast<uint16_t>(vb);
-                            *as_global(qv + 1) = static_cast<uint16_t>(vb >> 16);
-                        }
-                    }
-                }
-                fw[0] = wb[0] | (wb[1] << 16);
-                fw[1] = wb[2] | (wb[3] << 16);
-#pragma unroll
-                for (int s = 0; s < 4; s++) {
-                    fp[s] = f32_to_bits(p[s]);
-                    fm[s] = f32_to_bits(m[s]);
-                    fv[s] = f32_to_bits(v[s]);
-                }
-                // split first element: its first two bytes close the previous chunk and must not
-                // enter this tile's CRC of that stream
-                if (r == 0 && t.head_split && lane == head_lane) {
-                    uint32_t* const fx[3] = {fp, fm, fv};
-#pragma unroll
-                    for (int x = 1; x <= 3; x++) {
-                        if (t.head_split & (1u << x)) {
-#pragma unroll
-                            for (int s = 0; s < 4; s++) {
-                                if (s == head_sub) {
-                                    const uint32_t d = fx[x - 1][s];
-                                    // two message bytes in the low half are M(x) * x^16; their
-                                    // register is M(x) * x^32
-                                    add_head_piece(crcs, t, 3 + x, d & 0xFFFFu);
-                                    fx[x - 1][s] = d & 0xFFFF0000u;
-                                }
-                            }
+                        if (s == head_sub) {
+                            const uint32_t d = fx[x - 1][s];
+                            // two message bytes in the low half are M(x) * x^16; their register
+                            // is M(x) * x^32
+                            add_head_piece(crcs, t, 3 + x, d & 0xFFFFu);
+                            fx[x - 1][s] = d & 0xFFFF0000u;
                         }
                     }
                 }
             }
-            // copy for the folding wavefronts (zeros for a virtual row)
-            *reinterpret_cast<u32x2*>(&out.w[u][2 * lane]) = u32x2{fw[0], fw[1]};
-            *reinterpret_cast<u32x4*>(&out.p[u][4 * lane]) = u32x4{fp[0], fp[1], fp[2], fp[3]};
-            *reinterpret_cast<u32x4*>(&out.m[u][4 * lane]) = u32x4{fm[0], fm[1], fm[2], fm[3]};
-            *reinterpret_cast<u32x4*>(&out.v[u][4 * lane]) = u32x4{fv[0], fv[1], fv[2], fv[3]};
         }
-        __syncthreads();
+        *reinterpret_cast<u32x2*>(&out.w[u][2 * lane]) = u32x2{fw[0], fw[1]};
+        *reinterpret_cast<u32x4*>(&out.p[u][4 * lane]) = u32x4{fp[0], fp[1], fp[2], fp[3]};
+        *reinterpret_cast<u32x4*>(&out.m[u][4 * lane]) = u32x4{fm[0], fm[1], fm[2], fm[3]};
+        *reinterpret_cast<u32x4*>(&out.v[u][4 * lane]) = u32x4{fv[0], fv[1], fv[2], fv[3]};
+    };
+
+    // a full row from registers
+    auto full_row_step = [&](Batch& out, int r, const RowIn& cur) {
+        const int j0 = r * kRowElems + 4 * lane - G.pad_el;  // first element of the lane
+        uint32_t gb[4], wb[4];
+        float p[4], m[4], v[4];
+        gb[0] = cur.g.x & 0xFFFFu; gb[1] = cur.g.x >> 16;
+        gb[2] = cur.g.y & 0xFFFFu; gb[3] = cur.g.y >> 16;
+        p[0] = bits_to_f32(cur.p.x); p[1] = bits_to_f32(cur.p.y);
+        p[2] = bits_to_f32(cur.p.z); p[3] = bits_to_f32(cur.p.w);
+        m[0] = bits_to_f32(cur.m.x); m[1] = bits_to_f32(cur.m.y);
+        m[2] = bits_to_f32(cur.m.z); m[3] = bits_to_f32(cur.m.w);
+        v[0] = bits_to_f32(cur.v.x); v[1] = bits_to_f32(cur.v.y);
+        v[2] = bits_to_f32(cur.v.z); v[3] = bits_to_f32(cur.v.w);
+#pragma unroll
+        for (int s = 0; s < 4; s++) {
+            if constexpr (F16) nonfinite += f16_nonfinite(gb[s]) ? 1u : 0u;
+            adam_element<F16>(C, gb[s], p[s], m[s], v[s], wb[s]);
+        }
+        uint32_t fw[2] = {wb[0] | (wb[1] << 16), wb[2] | (wb[3] << 16)};
+        uint32_t fp[4], fm[4], fv[4];
+#pragma unroll
+        for (int s = 0; s < 4; s++) {
+            fp[s] = f32_to_bits(p[s]);
+            fm[s] = f32_to_bits(m[s]);
+            fv[s] = f32_to_bits(v[s]);
+        }
+        const u32x2 w2 = {fw[0], fw[1]};
+        const u32x4 po = {fp[0], fp[1], fp[2], fp[3]};
+        const u32x4 mo = {fm[0], fm[1], fm[2], fm[3]};
+        const u32x4 vo = {fv[0], fv[1], fv[2], fv[3]};
+        store8_unaligned<true>(tw + 2 * j0, w2);
+        store16_unaligned<true>(tp + 4 * j0, po);
+        store16_unaligned<true>(tm + 4 * j0, mo);
+        store16_unaligned<true>(tv + 4 * j0, vo);
+        store8_unaligned<true>(sw + 2 * j0, w2);
+        store16_unaligned<true>(sp + 4 * j0, po);
+        store16_unaligned<true>(sm + 4 * j0, mo);
+        store16_unaligned<true>(sv + 4 * j0, vo);
+        publish(out, r, fw, fp, fm, fv);
+    };
+
+    // the partial first row of a tile: element by element; absent elements stay zero
+    auto partial_row_step = [&](Batch& out, int r) {
+        const int j0 = r * kRowElems + 4 * lane - G.pad_el;
+        uint32_t gb[4], wb[4];
+        float p[4], m[4], v[4];
+#pragma unroll
+        for (int s = 0; s < 4; s++) {
+            const int j = j0 + s;
+            gb[s] = 0; wb[s] = 0; p[s] = 0.f; m[s] = 0.f; v[s] = 0.f;
+            if (j >= 0) {
+                gb[s] = *as_global(reinterpret_cast<const uint16_t*>(tg + 2 * j));
+                p[s] = *as_global(reinterpret_cast<const float*>(tp + 4 * j));
+                m[s] = *as_global(reinterpret_cast<const float*>(tm + 4 * j));
+                v[s] = *as_global(reinterpret_cast<const float*>(tv + 4 * j));
+                if constexpr (F16) nonfinite += f16_nonfinite(gb[s]) ? 1u : 0u;
+                adam_element<F16>(C, gb[s], p[s], m[s], v[s], wb[s]);
+                *as_global(reinterpret_cast<uint16_t*>(tw + 2 * j)) = static_cast<uint16_t>(wb[s]);
+                *as_global(reinterpret_cast<float*>(tp + 4 * j)) = p[s];
+                *as_global(reinterpret_cast<float*>(tm + 4 * j)) = m[s];
+                *as_global(reinterpret_cast<float*>(tv + 4 * j)) = v[s];
+                *as_global(reinterpret_cast<uint16_t*>(sw + 2 * j)) = static_cast<uint16_t>(wb[s]);
+                // stream offsets of fp32 segments may be 2 mod 4: halfword stores
+                const uint32_t pb = f32_to_bits(p[s]), mb = f32_to_bits(m[s]), vb = f32_to_bits(v[s]);
+                uint16_t* qp = reinterpret_cast<uint16_t*>(sp + 4 * j);
+                uint16_t* qm = reinterpret_cast<uint16_t*>(sm + 4 * j);
+                uint16_t* qv = reinterpret_cast<uint16_t*>(sv + 4 * j);
+                *as_global(qp) = static_cast<uint16_t>(pb);
+                *as_global(qp + 1) = static_cast<uint16_t>(pb >> 16);
+                *as_global(qm) = static_cast<uint16_t>(mb);
+                *as_global(qm + 1) = static_cast<uint16_t>(mb >> 16);
+                *as_global(qv) = static_cast<uint16_t>(vb);
+                *as_global(qv + 1) = static_cast<uint16_t>(vb >> 16);
+            }
+        }
+        uint32_t fw[2] = {wb[0] | (wb[1] << 16), wb[2] | (wb[3] << 16)};
+        uint32_t fp[4], fm[4], fv[4];
+#pragma unroll
+        for (int s = 0; s < 4; s++) {
+            fp[s] = f32_to_bits(p[s]);
+            fm[s] = f32_to_bits(m[s]);
+            fv[s] = f32_to_bits(v[s]);
+        }
+        publish(out, r, fw, fp, fm, fv);
+    };
+
+    const int first = u - G.pad_rows;  // this wavefront's row of batch 0
+    const int nb = G.n_batches;
+    int b = 0;
+    if (!full_row(first)) {
+        // a virtual row (zeros) or the partial first row of the tile
+        if (first < 0) {
+            uint32_t zw[2] = {0, 0}, z4[4] = {0, 0, 0, 0};
+            publish(buf[0], first, zw, z4, z4, z4);
+        } else {
+            partial_row_step(buf[0], first);
+        }
+        __syncthreads();  // the barrier of batch 0
+        b = 1;
     }
+    // rows first + 4b', b' >= b, are full rows
+    RowIn qa, qb;  // inputs of batch b, b + 2, ... and of batch b + 1, b + 3, ...
+    qa = qb = RowIn{u32x2{0, 0}, u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}};
+    if (b < nb) load_row(first + kBatchRows * b, qa);
+    if (b + 1 < nb) load_row(first + kBatchRows * (b + 1), qb);
+    // one batch: take the inputs out of `q`, refill `q` for two batches later, update the row
+    auto batch_step = [&](int bb, RowIn& q, auto prefetch_c) {
+        const int r = first + kBatchRows * bb;
+        const RowIn cur = q;
+        if constexpr (decltype(prefetch_c)::value) load_row(r + 2 * kBatchRows, q);
+        full_row_step(buf[bb & 1], r, cur);
+        __syncthreads();
+    };
+    // steady part: the batches two ahead exist.  Its first round stands in front of the loop, so
+    // that the loop is entered with the same loads and stores in flight as on its back edge.
+    if (b + 3 < nb) {
+        batch_step(b, qa, std::true_type{});
+        batch_step(b + 1, qb, std::true_type{});
+        b += 2;
+    }
+    while (b + 3 < nb) {
+        batch_step(b, qa, std::true_type{});
+        batch_step(b + 1, qb, std::true_type{});
+        b += 2;
+    }
+    // up to three batches are left; only the first of three still has something to prefetch
+    const int left = nb - b;
+    if (left == 3) {
+        batch_step(b, qa, std::true_type{});
+        batch_step(b + 1, qb, std::false_type{});
+        batch_step(b + 2, qa, std::false_type{});
+    } else if (left == 2) {
+        batch_step(b, qa, std::false_type{});
+        batch_step(b + 1, qb, std::false_type{});
+    } else if (left == 1) {
+        batch_step(b, qa, std::false_type{});
+    }
+    __syncthreads();  // the folding wavefronts take the last batch after this one
+
     if constexpr (F16) {
         if (C.n_nonfinite) {
 #pragma unroll
