@@ -30,7 +30,8 @@ struct ff_plan {
     uint32_t affine = 0;  // preset/complement term of a chunk_bytes-long CRC
     // fused optimizer step (only when every parameter group is complete)
     const WorkTile* work = nullptr;
-    uint32_t n_work = 0;
+    uint32_t n_work = 0;        // all work tiles: parameter tiles first, then RAW tiles
+    uint32_t n_work_param = 0;
     uint64_t* grads = nullptr;        // [n_params] device copy of the caller's gradient pointers
     const uint32_t* fused_tabs = nullptr;
     // selective restore: device lists of the chosen tiles / chunks
@@ -109,6 +110,8 @@ int upload_tables(ff_plan* p)
     t.partial = reinterpret_cast<uint32_t*>(d + o_partial);
     p->work = reinterpret_cast<const WorkTile*>(d + o_work);
     p->n_work = static_cast<uint32_t>(work.size());
+    p->n_work_param = 0;
+    for (const WorkTile& w : work) p->n_work_param += (w.kind == kWorkParam) ? 1u : 0u;
     p->grads = reinterpret_cast<uint64_t*>(d + o_grads);
     p->fused_tabs = reinterpret_cast<const uint32_t*>(d + o_ftabs);
     p->sel_tiles = reinterpret_cast<uint32_t*>(d + o_selt);
@@ -370,7 +373,8 @@ int adam_impl(const ff_plan* p, const void* const* grads, const ff_adam_hparams*
             return hip_fail(e);
         }
     }
-    FF_HIP_TRY(launch_fused(half_dtype == FF_F16, p->work, p->n_work, p->grads, p->fused_tabs,
+    FF_HIP_TRY(launch_fused(half_dtype == FF_F16, p->work, p->n_work_param,
+                            p->n_work - p->n_work_param, p->grads, p->fused_tabs,
                             chunks, crcs, L.n_chunks, L.payload, L.buffer_bytes, p->affine, c, s));
     return FF_OK;
 }

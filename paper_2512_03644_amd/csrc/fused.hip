@@ -33,6 +33,9 @@ using RawFold = Fold16x10;  // RAW copy tiles
 constexpr int kPhases = 5;  // rows folded between two physical rotations of the state
 static_assert(kPhases <= RawFold::NE, "rotation step");
 constexpr int kRowElems = 256;
+constexpr int kRawRows = kRawTileBytes / 1024;  // rows of a whole RAW tile
+constexpr int kRawDepth = 16;                   // rows in flight on its straight-line path
+static_assert(kRawRows % F32Fold::NE == 0 && kRawDepth <= kRawRows, "whole RAW tile");
 
 __device__ __forceinline__ float bits_to_f32(uint32_t u) { return __uint_as_float(u); }
 __device__ __forceinline__ uint32_t f32_to_bits(float f) { return __float_as_uint(f); }
@@ -403,13 +406,36 @@ __device__ __forceinline__ void run_raw_tile(const WorkTile& t, uint8_t* __restr
                                              uint32_t* __restrict__ crcs, const FusedConsts& C,
                                              const Lds& lds, int lane)
 {
-    constexpr int NE = RawFold::NE;
     const int n = static_cast<int>(t.n);  // bytes, even
+    const uint8_t* const src = reinterpret_cast<const uint8_t*>(t.ptr[0]);
+    uint8_t* const dst = chunks + t.soff[0];
+    if (n == kRawRows * 1024) {
+        // a whole tile: straight-line code, kRawDepth rows in flight
+        uint32_t S[F32Fold::NE][4];
+        static_for<F32Fold::NE>([&](auto e) { static_for<4>([&](auto f) { S[e][f] = 0; }); });
+        u32x4 w[kRawDepth];
+        static_for<kRawDepth>(
+            [&](auto k) { w[k] = load16_unaligned<true>(src + k * 1024 + 16 * lane); });
+        static_for<kRawRows>([&](auto Jc) {
+            constexpr int J = Jc;
+            const u32x4 x = w[J % kRawDepth];
+            store16_unaligned<true>(dst + J * 1024 + 16 * lane, x);
+            const uint32_t d[4] = {x.x, x.y, x.z, x.w};
+            fold_row<F32Fold, J % F32Fold::NE>(S, d);
+            if constexpr (J + kRawDepth < kRawRows) {
+                __builtin_amdgcn_sched_barrier(0);
+                w[J % kRawDepth] = load16_unaligned<true>(src + (J + kRawDepth) * 1024 + 16 * lane);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+        const uint32_t reg = reduce_state<F32Fold>(S, lds.tab16, lds.lane16[lane]);
+        if (lane == 0) add_piece(crcs, t, 0, reg);
+        return;
+    }
+    constexpr int NE = RawFold::NE;
     const int pad_b = (1024 - n % 1024) % 1024;
     const int rows = (n + pad_b) / 1024;
     const int pad_rows = (kPhases - rows % kPhases) % kPhases;
-    const uint8_t* const src = reinterpret_cast<const uint8_t*>(t.ptr[0]);
-    uint8_t* const dst = chunks + t.soff[0];
 
     uint32_t S[NE][4];
     static_for<NE>([&](auto e) { static_for<4>([&](auto f) { S[e][f] = 0; }); });
@@ -472,12 +498,7 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
     // the tile descriptor is uniform and read-only: the loads below go through scalar registers
     // (a private copy indexed by the stream number would live in scratch memory instead)
     const WorkTile& t = tiles[ti];
-    if (t.kind != kWorkParam) {
-        // RAW bytes: one wavefront copies and folds, the others just leave
-        __syncthreads();  // tables complete
-        if (wave == 0) run_raw_tile(t, chunks, crcs, C, lds, lane);
-        return;
-    }
+    if (t.kind != kWorkParam) return;  // RAW tiles belong to raw_kernel
     // every wavefront of the workgroup passes the same n_batches + 1 barriers
     const TileGeom G = tile_geom(t);
     if (wave < kUpdateWaves) {
@@ -492,6 +513,24 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
             reg = fold_stream<F32Fold, 4>(G, buf, x, lane, lds.tab16, lds.lane16);
         if (lane == 0) add_piece(crcs, t, x, reg);
     }
+}
+
+// RAW tiles: one wavefront per tile copies its bytes into the snapshot and folds them.
+constexpr int kRawWaves = 4;
+__global__ __launch_bounds__(kWaveSize* kRawWaves) void raw_kernel(
+    const WorkTile* __restrict__ tiles, uint32_t n_tiles, const uint32_t* __restrict__ tabs,
+    uint8_t* __restrict__ chunks, uint32_t* __restrict__ crcs, FusedConsts C)
+{
+    __shared__ Lds lds;
+    for (int i = threadIdx.x; i < 1024; i += blockDim.x) lds.tab16[i] = tabs[i];
+    if (threadIdx.x < kWaveSize) lds.lane16[threadIdx.x] = tabs[2048 + threadIdx.x];
+    __syncthreads();
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const uint32_t ti = blockIdx.x * kRawWaves + __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
+    if (ti >= n_tiles) return;
+    const WorkTile& t = tiles[ti];
+    if (t.kind != kWorkRaw) return;
+    run_raw_tile(t, chunks, crcs, C, lds, lane);
 }
 
 // crcs[] = the preset/complement term (the tiles XOR their pieces into it), the tail of the last
@@ -523,7 +562,8 @@ void build_fused_tabs(uint32_t* tab)
     }
 }
 
-hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_tiles, const uint64_t* grads,
+hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_param_tiles,
+                        uint32_t n_raw_tiles, const uint64_t* grads,
                         const uint32_t* tabs, void* chunks, uint32_t* crcs, uint64_t n_chunks,
                         uint64_t payload, uint64_t buffer_bytes, uint32_t affine,
                         const FusedConsts& consts, hipStream_t stream)
@@ -538,14 +578,21 @@ hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_tiles, const
                        affine, c, payload, buffer_bytes, f16 ? consts.n_nonfinite : nullptr);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (n_tiles) {
-        const unsigned grid = n_tiles;
+    if (n_param_tiles) {
+        const unsigned grid = n_param_tiles;
         if (f16)
             hipLaunchKernelGGL(fused_kernel<true>, dim3(grid), dim3(kWaveSize * kWavesPerBlock), 0,
-                               stream, tiles, n_tiles, grads, tabs, c, crcs, consts);
+                               stream, tiles, n_param_tiles, grads, tabs, c, crcs, consts);
         else
             hipLaunchKernelGGL(fused_kernel<false>, dim3(grid), dim3(kWaveSize * kWavesPerBlock), 0,
-                               stream, tiles, n_tiles, grads, tabs, c, crcs, consts);
+                               stream, tiles, n_param_tiles, grads, tabs, c, crcs, consts);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (n_raw_tiles) {
+        const unsigned grid = (n_raw_tiles + kRawWaves - 1) / kRawWaves;
+        hipLaunchKernelGGL(raw_kernel, dim3(grid), dim3(kWaveSize * kRawWaves), 0, stream,
+                           tiles + n_param_tiles, n_raw_tiles, tabs, c, crcs, consts);
         e = hipGetLastError();
     }
     return e;

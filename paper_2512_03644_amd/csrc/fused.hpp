@@ -26,8 +26,10 @@ void build_fused_tabs(uint32_t* tab);
 
 // Enqueues prepare (crcs = affine, zero tail, counter = 0) and the tile kernel.
 // tiles/grads/tabs: device tables (tabs = tables for 1024-byte rows, then for 512-byte rows).
-// f16: gradients and working weights are fp16 (else bf16).
-hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_tiles, const uint64_t* grads,
+// f16: gradients and working weights are fp16 (else bf16).  tiles: the parameter tiles first, then
+// the RAW tiles (a kernel of their own).
+hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_param_tiles,
+                        uint32_t n_raw_tiles, const uint64_t* grads,
                         const uint32_t* tabs, void* chunks, uint32_t* crcs, uint64_t n_chunks,
                         uint64_t payload, uint64_t buffer_bytes, uint32_t affine,
                         const FusedConsts& consts, hipStream_t stream);

@@ -57,9 +57,10 @@ struct WorkTile {
 
 constexpr uint32_t kWorkParam = 0, kWorkRaw = 1;
 constexpr uint32_t kParamTileElems = 1u << 13;
-constexpr uint32_t kRawTileBytes = 1u << 18;
+constexpr uint32_t kRawTileBytes = 1u << 15;
 
-// Work list of the fused step over the whole layout (needs L.adam_ok).
+// Work list of the fused step over the whole layout (needs L.adam_ok): the parameter tiles first,
+// then the RAW tiles.
 void build_work_tiles(const Layout& L, std::vector<WorkTile>& out);
 
 // Returns FF_OK or a negative ff_status; `out` is valid only on FF_OK.
