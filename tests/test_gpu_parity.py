@@ -757,3 +757,58 @@ def test_pack_to_host_equals_pack(oracle, slice_chunks):
     assert np.array_equal(h_crcs.numpy().view(np.uint32), want_crcs)
     assert np.array_equal(chunks.cpu().numpy(), want_buf)       # the device staging holds it too
     assert np.array_equal(_u32(crcs), want_crcs)
+
+
+# ---- the calls together: a worker's step, a damaged transfer, a newcomer's recovery -----------------
+
+def test_failover_scenario(oracle):
+    """Section 3.1, steps 5-6, with this library's pieces: a worker takes an optimizer step that
+    snapshots its state; the snapshot reaches a newcomer with a few chunks damaged; the newcomer
+    loads what verified, asks for the damaged chunks again and loads those; its state then equals
+    the worker's, which equals the oracle's."""
+    numels = [30000, 70001, 4096, 123457]
+    C = 1 << 16
+    worker = wl.param_shard("w", numels, C, 41, DEV, with_grads=True)
+    host = [wl.to_numpy_bytes(t) for t in worker.segments]
+    params_np = [(host[4 * i].view(np.uint16), host[4 * i + 1].view(np.float32),
+                  host[4 * i + 2].view(np.float32), host[4 * i + 3].view(np.float32))
+                 for i in range(len(numels))]
+    grads_np = [wl.to_numpy_bytes(p.grad).view(np.uint16) for p in worker.params]
+    plan = ff.plan_for_shard(worker)
+    chunks, crcs, _, _ = ff.alloc_outputs(plan, DEV)
+    ff.ff_adam_step_snapshot(plan, [p.grad for p in worker.params], HP, chunks, crcs)
+    torch.cuda.synchronize()
+    want_buf, want_crcs = oracle.adam_snapshot(params_np, grads_np, host, C, HP)
+    assert np.array_equal(chunks.cpu().numpy(), want_buf) and np.array_equal(_u32(crcs), want_crcs)
+
+    # the newcomer: same layout (checked through the layout id), empty tensors
+    newcomer = wl.param_shard("n", numels, C, 99, DEV)
+    _poison_segments(newcomer)
+    plan_n = ff.plan_for_shard(newcomer)
+    assert plan_n.layout_id == plan.layout_id and plan_n.num_chunks == plan.num_chunks
+    received = chunks.clone()
+    damaged = [1, plan.num_chunks // 2, plan.num_chunks - 1]
+    for j in damaged:
+        received[j * C + 100 + j] ^= 0x10
+    _, _, bad, n_bad = ff.alloc_outputs(plan_n, DEV)
+    ff.ff_restore(plan_n, received, crcs, bad, n_bad, flags=ff.FF_RESTORE_SKIP_BAD)
+    torch.cuda.synchronize()
+    again = torch.nonzero(bad).flatten().tolist()
+    assert again == damaged and int(n_bad.item()) == len(damaged)
+    # which tensor ranges are still missing: the spans of the bad chunks hold the poison
+    stream = _segments_as_stream(newcomer)
+    for j in range(plan.num_chunks):
+        first, n, begin, end = plan_n.chunk_span(j)
+        if j in damaged:
+            assert bool((stream[begin:end] == 0xA5).all())
+        else:
+            assert np.array_equal(stream[begin:end], want_buf[begin:end])
+    # the sender transmits the damaged chunks again
+    for j in again:
+        received[j * C:(j + 1) * C] = chunks[j * C:(j + 1) * C]
+    ff.ff_restore_chunks(plan_n, received, crcs, again, bad, n_bad)
+    torch.cuda.synchronize()
+    assert int(n_bad.item()) == 0
+    for a, b in zip(newcomer.segments, worker.segments):
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+    assert np.array_equal(_segments_as_stream(newcomer), want_buf[:plan.payload_bytes])
