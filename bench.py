@@ -61,6 +61,11 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-adam", action="store_true", help="leave the fused optimizer step out")
     ap.add_argument("--tile-log2", type=int, default=0, help="tuning: log2 of the tile size")
+    ap.add_argument("--workload", default="llama7b",
+                    choices=["llama7b", "llama70b", "fragmented", "tiny"],
+                    help="llama7b is the headline shard; the others are the remaining "
+                         "configurations, timed the same way (fused step where the shard has "
+                         "parameter groups and gradients)")
     return ap.parse_args()
 
 
@@ -135,12 +140,20 @@ def main():
     torch.cuda.set_device(0)
     ff.lib()
 
-    with_adam = not args.no_adam
-    shard = wl.config_llama7b(dev, with_grads=with_adam)
+    with_adam = not args.no_adam and args.workload == "llama7b"
+    if args.workload == "llama7b":
+        shard = wl.config_llama7b(dev, with_grads=with_adam)
+    elif args.workload == "llama70b":
+        shard = wl.config_llama70b(dev)
+    elif args.workload == "fragmented":
+        shard = wl.config_fragmented(dev)
+    else:
+        shard = wl.config_tiny(dev)
     plan = ff.plan_for_shard(shard, tile_log2=args.tile_log2)
     chunks, crcs, bad, n_bad = ff.alloc_outputs(plan, dev)
     N = plan.payload_bytes
     n_el = sum(p.master.numel() for p in shard.params)
+    n_cpu_groups = 48 if args.workload == "llama7b" else 0
     hp = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1000)
     grads = [p.grad for p in shard.params] if with_adam else None
 
@@ -198,9 +211,10 @@ def main():
     detail["pack"]["payload_GBps"] = round(N / detail["pack"]["avg_ms"] / 1e6, 1)
     detail["restore"]["payload_GBps"] = round(N / detail["restore"]["avg_ms"] / 1e6, 1)
     # the plain-copy ceiling of the same byte count, printed beside the real kernels
-    src = torch.empty(N, dtype=torch.uint8, device=dev)
-    ts = event_ms(lambda: ff.ff_copy_ceiling(chunks, src, N), 5, torch)
-    copy_gbs = 2 * N / (sum(ts) / len(ts)) / 1e6
+    n_copy = N // 16 * 16
+    src = torch.empty(n_copy, dtype=torch.uint8, device=dev)
+    ts = event_ms(lambda: ff.ff_copy_ceiling(chunks, src, n_copy), 5, torch)
+    copy_gbs = 2 * n_copy / (sum(ts) / len(ts)) / 1e6
     del src
     for name in detail:
         detail[name]["frac_of_copy_ceiling"] = round(detail[name]["traffic_GBps"] / copy_gbs, 4)
@@ -213,25 +227,36 @@ def main():
     achieved = kbytes / detail[dom]["avg_ms"] / 1e6
     roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic(kname),
+                "traffic": measured_traffic(kname) if args.workload == "llama7b" else None,
                 "algorithmic_bytes_per_launch": kbytes,
                 "avg_launch_ms": detail[dom]["avg_ms"],
                 "copy_ceiling_GBps": round(copy_gbs, 1)}
 
-    out = {"metric": "snapshot pack+CRC and restore GB/s, % of HBM peak, 7B-shaped shard",
+    # verify-only (what a receiver runs on arrival): reported beside the step, not part of it
+    ts = event_ms(lambda: ff.ff_restore(plan, chunks, crcs, bad, n_bad,
+                                        flags=ff.FF_RESTORE_VERIFY_ONLY), 5, torch)
+    verify_ms = sum(ts) / len(ts)
+    extra = {"verify_only": {"avg_ms": round(verify_ms, 4),
+                             "payload_GBps": round(N / verify_ms / 1e6, 1),
+                             "frac_of_peak": round(N / verify_ms / 1e6 / HBM_PEAK_GBS, 4)}}
+    metric = "snapshot pack+CRC and restore GB/s, % of HBM peak, 7B-shaped shard"
+    if args.workload != "llama7b":
+        metric = "snapshot pack+CRC and restore GB/s, %% of HBM peak, %s shard" % args.workload
+    out = {"metric": metric,
            "value": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": "f32" if with_adam else "u8", "data": "synthetic",
-           "config": {"workload": "llama7b-dp8 shard: 226 params, bf16 w + fp32 master/m/v, "
-                                  "%d B payload, 904 segments, 4 MiB chunks (%d)"
-                                  % (N, plan.num_chunks),
+           "config": {"workload": "%s shard: %d parameter groups, %d B payload, %d segments, "
+                                  "%d KiB chunks (%d)"
+                                  % (shard.name, len(shard.params), N, plan.num_segments,
+                                     plan.chunk_bytes // 1024, plan.num_chunks),
                       "step": " + ".join(n for n, _, _ in ops),
                       "bytes_per_step": step_bytes},
            "pct_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS * 100, 2),
-           "ops": detail, "roofline": roofline}
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(shard, 48, hp, with_adam, torch)
+           "ops": detail, "extra": extra, "roofline": roofline}
+    if not args.no_cpu_baseline and n_cpu_groups:
+        out["cpu_baseline"] = cpu_baseline(shard, n_cpu_groups, hp, with_adam, torch)
     print(json.dumps(out))
 
 
