@@ -1,8 +1,9 @@
 // Fused optimizer step + snapshot for gfx950.
 //
-// A workgroup owns one work tile (layout.hpp): a run of up to kParamTileElems elements of one parameter
-// group, or a run of bytes of a RAW segment.  A parameter tile is walked in rows of 256
-// elements, lane l taking 4 consecutive elements: 8 bytes of bf16 gradient and 3 x 16 bytes of
+// Work tiles (layout.hpp) are runs of up to kParamTileElems elements of one parameter group, one
+// workgroup each, and runs of up to kRawTileBytes of a RAW segment, one wavefront each in a
+// kernel of their own that only copies and folds.  A parameter tile is walked in rows of 256
+// elements, lane l taking 4 consecutive elements: 8 bytes of 16-bit gradient and 3 x 16 bytes of
 // fp32 master/m/v come in, the AdamW update runs in registers, and the four results go out
 // twice -- in place, and at their stream offsets in the chunk buffer -- plus once into LDS,
 // from where four folding wavefronts (one per output stream) take them into their CRC states,
@@ -403,8 +404,7 @@ __device__ __forceinline__ uint32_t fold_stream(const TileGeom& G, Batch (&buf)[
 // ---- RAW tile: plain copy into the snapshot -----------------------------------------------------
 
 __device__ __forceinline__ void run_raw_tile(const WorkTile& t, uint8_t* __restrict__ chunks,
-                                             uint32_t* __restrict__ crcs, const FusedConsts& C,
-                                             const Lds& lds, int lane)
+                                             uint32_t* __restrict__ crcs, const Lds& lds, int lane)
 {
     const int n = static_cast<int>(t.n);  // bytes, even
     const uint8_t* const src = reinterpret_cast<const uint8_t*>(t.ptr[0]);
@@ -519,7 +519,7 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
 constexpr int kRawWaves = 4;
 __global__ __launch_bounds__(kWaveSize* kRawWaves) void raw_kernel(
     const WorkTile* __restrict__ tiles, uint32_t n_tiles, const uint32_t* __restrict__ tabs,
-    uint8_t* __restrict__ chunks, uint32_t* __restrict__ crcs, FusedConsts C)
+    uint8_t* __restrict__ chunks, uint32_t* __restrict__ crcs)
 {
     __shared__ Lds lds;
     for (int i = threadIdx.x; i < 1024; i += blockDim.x) lds.tab16[i] = tabs[i];
@@ -530,7 +530,7 @@ __global__ __launch_bounds__(kWaveSize* kRawWaves) void raw_kernel(
     if (ti >= n_tiles) return;
     const WorkTile& t = tiles[ti];
     if (t.kind != kWorkRaw) return;
-    run_raw_tile(t, chunks, crcs, C, lds, lane);
+    run_raw_tile(t, chunks, crcs, lds, lane);
 }
 
 // crcs[] = the preset/complement term (the tiles XOR their pieces into it), the tail of the last
@@ -592,7 +592,7 @@ hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_param_tiles,
     if (n_raw_tiles) {
         const unsigned grid = (n_raw_tiles + kRawWaves - 1) / kRawWaves;
         hipLaunchKernelGGL(raw_kernel, dim3(grid), dim3(kWaveSize * kRawWaves), 0, stream,
-                           tiles + n_param_tiles, n_raw_tiles, tabs, c, crcs, consts);
+                           tiles + n_param_tiles, n_raw_tiles, tabs, c, crcs);
         e = hipGetLastError();
     }
     return e;

@@ -166,10 +166,15 @@ __device__ __forceinline__ void fold_word(uint32_t (&S)[kNE][kNF], u32x4 w)
 
 // ---- tile kernel -------------------------------------------------------------------------------
 
-// Rows are handled in groups of kNE (one full rotation of the state registers).  A group whose
-// rows, and the rows it prefetches, all lie inside one segment runs as straight-line code: no
-// branch sits between the loads, so up to kDepth of them stay in flight per wavefront.  Any other
-// group (tile start with virtual rows, segment boundary, end of payload) takes the guarded path.
+// Three bodies, fastest first.  (1) A default-size tile that lies inside one segment (and a
+// read-only tile of the grouped size) is one piece of straight-line code over all its rows.
+// (2) A default-size tile that touches up to four segments or the end of the payload is
+// straight-line too, every lane choosing its segment by comparisons.  (3) Everything else -- other
+// tile sizes, many small segments, tiles behind the payload -- walks its rows in groups of kNE (one
+// full rotation of the state registers): a group whose rows, and the rows it prefetches, all lie
+// inside one segment runs without branches between its loads, kDepth of them in flight; any other
+// group (virtual rows at the tile start, a segment boundary, the end of the payload) takes the
+// guarded path row by row.
 template <int MODE, int HINT>
 __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
     const uint64_t* __restrict__ seg_off, const uint64_t* __restrict__ seg_ptr,
