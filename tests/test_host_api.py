@@ -239,3 +239,11 @@ def test_random_layouts_agree_with_the_definition(oracle):
             assert list(range(first, first + n)) == want
 
     check()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    run = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                         capture_output=True, text=True, timeout=120)
+    assert run.returncode == 2 and "one GPU" in run.stderr and run.stdout.strip() == ""
