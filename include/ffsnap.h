@@ -87,9 +87,12 @@ typedef struct {
  *   bits 8..15   log2 of the tile size in bytes (the stream range one wavefront folds; clamped to
  *                [10, log2(chunk_bytes)]; default 15)
  *   bits 16..18  bit 18 set: bits 16..17 choose non-temporal accesses on the tensor side (bit 16)
- *                and on the chunk-buffer side (bit 17); default both                             */
+ *                and on the chunk-buffer side (bit 17); default both
+ *   bits 19..23  order in which workgroups take tiles: 0 = default, n in 1..30 = every XCD takes
+ *                runs of 2^(n-1) consecutive workgroup tiles, 31 = plain launch order            */
 #define FF_PLAN_TILE_LOG2(n) (((uint32_t)(n) & 0xFFu) << 8)
 #define FF_PLAN_CACHE_HINT(h) (0x40000u | (((uint32_t)(h) & 3u) << 16))
+#define FF_PLAN_XCD_ORDER(n) (((uint32_t)(n) & 31u) << 19)
 
 /* ff_restore flags */
 #define FF_RESTORE_VERIFY_ONLY 1u /* recompute and compare CRCs, write bad[]/n_bad, scatter nothing */

@@ -32,6 +32,7 @@ struct ff_plan {
     const WorkTile* work = nullptr;
     uint32_t n_work = 0;        // all work tiles: parameter tiles first, then RAW tiles
     uint32_t n_work_param = 0;
+    uint32_t fused_xcd_group = 4;  // XCD-aware order of the fused step's tiles (kernels.hpp)
     uint64_t* grads = nullptr;        // [n_params] device copy of the caller's gradient pointers
     const uint32_t* fused_tabs = nullptr;
     // selective restore: device lists of the chosen tiles / chunks
@@ -141,7 +142,7 @@ int ff_snapshot_plan(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_byt
     *out = nullptr;
     // bits 8..15 of flags: log2 of the tile size in bytes (0 = default), a tuning knob
     const unsigned tile_log2 = (flags >> 8) & 0xFFu;
-    if (flags & ~(FF_PLAN_HOST_ONLY | 0xFF00u | 0x70000u)) return FF_ERR_INVALID;
+    if (flags & ~(FF_PLAN_HOST_ONLY | 0xFF00u | 0x70000u | 0xF80000u)) return FF_ERR_INVALID;
     ff_plan* p = new (std::nothrow) ff_plan();
     if (!p) return FF_ERR_NOMEM;
     int rc;
@@ -172,6 +173,12 @@ int ff_snapshot_plan(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_byt
     t.tiles_per_chunk = L.tiles_per_chunk;
     // bits 16..18: bit 18 set = take bits 16..17 as the cache-hint selector (tuning knob)
     if (flags & 0x40000u) t.hint = (flags >> 16) & 3u;
+    // bits 19..23: 0 = default, else log2(xcd_group) + 1, 31 = no regrouping (tuning knob)
+    {
+        const unsigned xg = (flags >> 19) & 31u;
+        if (xg == 31u) t.xcd_group = p->fused_xcd_group = 0;
+        else if (xg) t.xcd_group = p->fused_xcd_group = 1u << (xg - 1);
+    }
     if (L.n_tiles > 0xFFFFFFF0ull) {
         delete p;
         return FF_ERR_INVALID;
@@ -350,6 +357,7 @@ int adam_impl(const ff_plan* p, const void* const* grads, const ff_adam_hparams*
         c.adam.eps = hp->eps;
     }
     c.inv_scale = inv_scale;
+    c.xcd_group = p->fused_xcd_group;
     c.n_nonfinite = n_nonfinite;
     // The device table of gradient pointers is refreshed only when a pointer differs from the last
     // call's (a training loop passes the same buffers every step).  The array is copied into the

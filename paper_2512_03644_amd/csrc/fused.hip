@@ -480,7 +480,7 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
     __shared__ Batch buf[2];
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
-    const uint32_t ti = blockIdx.x;  // one tile per workgroup
+    const uint32_t ti = xcd_order(blockIdx.x, gridDim.x, C.xcd_group);  // one tile per workgroup
     if (ti >= n_tiles) return;
     // The reduction tables are used after the last barrier of a tile only (every tile passes at
     // least two), so the folding wavefronts fetch them while the updating wavefronts are already

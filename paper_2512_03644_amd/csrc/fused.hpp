@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "kernels.hpp"
 #include "layout.hpp"
 
 namespace ffsnap {
@@ -16,6 +17,7 @@ struct FusedConsts {
     AdamConsts adam;
     float inv_scale = 1.0f;            // fp16 variant: reciprocal of the loss scale
     uint64_t* n_nonfinite = nullptr;   // fp16 variant: device counter of inf/NaN gradients, or null
+    uint32_t xcd_group = 0;            // XCD-aware order of the work tiles (see kernels.hpp)
 };
 
 // Device table of the fused kernels (kFusedTabWords entries): byte tables of multiplication by

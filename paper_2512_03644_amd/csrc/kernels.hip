@@ -189,7 +189,7 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
 
     const int lane = threadIdx.x & (kWaveSize - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
-    const uint32_t slot = blockIdx.x * kWavesPerBlock + wave;
+    const uint32_t slot = xcd_order(blockIdx.x, gridDim.x, T.xcd_group) * kWavesPerBlock + wave;
     if (slot >= (T.n_list ? T.n_list : T.n_tiles)) return;
     const uint32_t tile = T.tile_list ? __builtin_amdgcn_readfirstlane(T.tile_list[slot])
                                       : T.tile_begin + slot;

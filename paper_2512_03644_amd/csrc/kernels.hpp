@@ -27,7 +27,23 @@ struct TileTables {
     uint32_t tile_begin = 0;
     const uint32_t* skip_bad = nullptr;       // if set: bad[] per chunk; tiles of bad chunks are left out
     uint32_t tiles_per_chunk = 1;
+    // Workgroups are dealt to the 8 XCDs round-robin.  With xcd_group = G > 0 the workgroups of
+    // one XCD take G consecutive groups of tiles, the next XCD the following G, and so on, so
+    // that every XCD (and its L2) sweeps runs of G * 128 KiB instead of every eighth 128 KiB.
+    uint32_t xcd_group = 8;  // measured best of 0, 8 .. 8192 (restore +5 %, pack +2 %)
 };
+
+// Position in the work list of workgroup `b` of `n` under the XCD-aware order described at
+// TileTables::xcd_group (a bijection on [0, n); identity when g == 0).
+__host__ __device__ inline uint32_t xcd_order(uint32_t b, uint32_t n, uint32_t g)
+{
+    constexpr uint32_t kXcds = 8;
+    if (g == 0) return b;
+    const uint32_t span = kXcds * g;       // workgroups in one round over the XCDs
+    if (b >= n / span * span) return b;    // the incomplete last round keeps its order
+    const uint32_t round = b / span, in = b % span;
+    return round * span + (in % kXcds) * g + in / kXcds;
+}
 
 enum TileMode { kPack = 0, kRestore = 1, kVerify = 2 };
 
