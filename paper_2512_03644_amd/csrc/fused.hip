@@ -526,7 +526,9 @@ __global__ __launch_bounds__(kWaveSize* kRawWaves) void raw_kernel(
     if (threadIdx.x < kWaveSize) lds.lane16[threadIdx.x] = tabs[2048 + threadIdx.x];
     __syncthreads();
     const int lane = threadIdx.x & (kWaveSize - 1);
-    const uint32_t ti = blockIdx.x * kRawWaves + __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
+    // consecutive tiles per XCD, as in the tile kernel (a RAW tile is a 32 KiB copy as well)
+    const uint32_t ti = xcd_order(blockIdx.x, gridDim.x, 8) * kRawWaves +
+                        __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
     if (ti >= n_tiles) return;
     const WorkTile& t = tiles[ti];
     if (t.kind != kWorkRaw) return;
