@@ -81,9 +81,9 @@ def event_ms(fn, n, torch):
     return [a.elapsed_time(b) for a, b in evs]
 
 
-def cpu_baseline(shard, n_params, hp, with_adam, torch):
-    """The oracle's step (AdamW update, pack, restore) on the first n_params parameter groups of
-    the shard, chunk ranges and parameters spread over the host cores by a thread pool."""
+def cpu_oracle_step(shard, n_params, hp, with_adam, cores):
+    """One oracle step (AdamW update + pack, pack, restore) on the first n_params parameter groups
+    of the shard with `cores` threads: (step bytes, payload bytes, the three wall times)."""
     from concurrent.futures import ThreadPoolExecutor
     import numpy as np
     import oracle
@@ -95,7 +95,6 @@ def cpu_baseline(shard, n_params, hp, with_adam, torch):
     segs = [a for g in groups for a in g]
     nbytes = sum(s.size for s in segs)
     n_el = sum(g[1].size // 4 for g in groups)
-    cores = min(16, len(os.sched_getaffinity(0)))
     oracle.lib()
     t0 = time.perf_counter()
     if with_adam:
@@ -114,13 +113,29 @@ def cpu_baseline(shard, n_params, hp, with_adam, torch):
     t3 = time.perf_counter()
     assert n_bad == 0
     step_bytes = 4 * nbytes + (42 * n_el if with_adam else 0)
-    return {"value": round(step_bytes / (t3 - t0) / 1e9, 3), "unit": "GB/s", "cores": cores,
+    return step_bytes, nbytes, (t1 - t0, t2 - t1, t3 - t2)
+
+
+def cpu_baseline(shard, n_params, hp, with_adam, torch):
+    """The oracle's step on a bounded sample of the shard: on all host cores available to the
+    process (chunk ranges and parameters spread by a thread pool) and, on a smaller sample, on
+    one core."""
+    cores = min(16, len(os.sched_getaffinity(0)))
+    step_bytes, nbytes, t = cpu_oracle_step(shard, n_params, hp, with_adam, cores)
+    n_one = max(1, min(n_params, 6))
+    one_bytes, one_payload, t_one = cpu_oracle_step(shard, n_one, hp, with_adam, 1)
+    what = "oracle %spack, restore; bytes counted as for the GPU step" % (
+        "AdamW update + pack (unfused), " if with_adam else "")
+    return {"value": round(step_bytes / sum(t) / 1e9, 3), "unit": "GB/s", "cores": cores,
             "kind": "oracle",
-            "sample": "first %d of %d parameter groups of the same shard (%.2f GB payload): oracle "
-                      "%spack, restore; bytes counted as for the GPU step; wall %.2f + %.2f + "
-                      "%.2f s" % (n_params, len(shard.params), nbytes / 1e9,
-                                  "AdamW update + pack (unfused), " if with_adam else "",
-                                  t1 - t0, t2 - t1, t3 - t2)}
+            "sample": "first %d of %d parameter groups of the same shard (%.2f GB payload): %s; "
+                      "wall %.2f + %.2f + %.2f s" % ((n_params, len(shard.params), nbytes / 1e9,
+                                                      what) + t),
+            "single_thread": {"value": round(one_bytes / sum(t_one) / 1e9, 3), "unit": "GB/s",
+                              "cores": 1,
+                              "sample": "first %d parameter groups (%.2f GB payload), same steps; "
+                                        "wall %.2f + %.2f + %.2f s"
+                                        % ((n_one, one_payload / 1e9) + t_one)}}
 
 
 def main():
