@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 
 
 KERNEL_SOURCES = ("kernels.hip", "kernels.hpp", "fused.hip", "fused.hpp", "fold.h", "fold_taps.h",
-                  "gf2.h", "layout.hpp")
+                  "gf2.h", "layout.hpp", "xcd_order.h")
 
 
 def kernel_source_hash():

@@ -17,6 +17,22 @@ FF_ERR_NOMEM, FF_ERR_HIP, FF_ERR_HOST_ONLY = -4, -5, -6
 FF_BF16, FF_F32, FF_F16 = 1, 2, 3
 FF_KIND_RAW, FF_KIND_W16, FF_KIND_MASTER, FF_KIND_M, FF_KIND_V = 0, 1, 2, 3, 4
 FF_PLAN_HOST_ONLY = 1
+
+
+def FF_PLAN_TILE_LOG2(n):
+    """Plan flag: tile size 2^n bytes (tuning knob; 0 = default)."""
+    return (n & 0xFF) << 8
+
+
+def FF_PLAN_CACHE_HINT(h):
+    """Plan flag: bit 0 of h = non-temporal tensor-side accesses, bit 1 = buffer side."""
+    return 0x40000 | ((h & 3) << 16)
+
+
+def FF_PLAN_XCD_ORDER(n):
+    """Plan flag: every XCD takes runs of 2^(n-1) workgroup tiles (0 = default, 31 = launch order)."""
+    return (n & 31) << 19
+
 FF_RESTORE_VERIFY_ONLY = 1
 FF_RESTORE_SKIP_BAD = 2
 

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "xcd_order.h"
+
 namespace ffsnap {
 
 // Device-side view of a plan's tables, plus the constants the tile kernels need.
@@ -32,18 +34,6 @@ struct TileTables {
     // that every XCD (and its L2) sweeps runs of G * 128 KiB instead of every eighth 128 KiB.
     uint32_t xcd_group = 8;  // measured best of 0, 8 .. 8192 (restore +5 %, pack +2 %)
 };
-
-// Position in the work list of workgroup `b` of `n` under the XCD-aware order described at
-// TileTables::xcd_group (a bijection on [0, n); identity when g == 0).
-__host__ __device__ inline uint32_t xcd_order(uint32_t b, uint32_t n, uint32_t g)
-{
-    constexpr uint32_t kXcds = 8;
-    if (g == 0) return b;
-    const uint32_t span = kXcds * g;       // workgroups in one round over the XCDs
-    if (b >= n / span * span) return b;    // the incomplete last round keeps its order
-    const uint32_t round = b / span, in = b % span;
-    return round * span + (in % kXcds) * g + in / kXcds;
-}
 
 enum TileMode { kPack = 0, kRestore = 1, kVerify = 2 };
 

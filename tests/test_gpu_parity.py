@@ -23,8 +23,8 @@ def _u32(t):
     return t.cpu().numpy().view(np.uint32)
 
 
-def _pack_and_compare(shard, oracle, tile_log2=0):
-    plan = ff.plan_for_shard(shard, tile_log2=tile_log2)
+def _pack_and_compare(shard, oracle, tile_log2=0, flags=0):
+    plan = ff.plan_for_shard(shard, flags=flags, tile_log2=tile_log2)
     chunks, crcs, bad, n_bad = ff.alloc_outputs(plan, DEV)
     chunks.fill_(0xA5)                       # every byte must be written, zero tail included
     crcs.fill_(-1)
@@ -307,7 +307,7 @@ HP = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1000)
 
 
 def _adam_and_compare(oracle, numels, chunk, seed, hp=HP, extra_raw=None, half=torch.bfloat16,
-                      loss_scale=1.0):
+                      loss_scale=1.0, flags=0):
     """Runs ff_adam_step_snapshot and the oracle's unfused definition (update, then pack) on the
     same inputs.  fp32 state: max relative error <= 1e-6 is the acceptance bound; the fixed
     operation order makes the two bit-identical, which is what is asserted.  16-bit weights: exact
@@ -325,7 +325,7 @@ def _adam_and_compare(oracle, numels, chunk, seed, hp=HP, extra_raw=None, half=t
             tensors.insert(pos, t)
             kinds.insert(pos, ff.FF_KIND_RAW)
             pids.insert(pos, 0)
-    plan = ff.ff_snapshot_plan(tensors, chunk, kinds=kinds, param_ids=pids)
+    plan = ff.ff_snapshot_plan(tensors, chunk, flags=flags, kinds=kinds, param_ids=pids)
     assert plan.num_params == len(numels)
     # host copies for the oracle, taken before the in-place update
     host = [wl.to_numpy_bytes(t) for t in tensors]
@@ -564,6 +564,44 @@ def test_pack_restore_random_layouts_and_tiles(oracle, seed):
     shard = wl.fragmented_shard(lay, chunk, seed=seed, device=DEV)
     state = _pack_and_compare(shard, oracle, tile_log2)
     _restore_and_compare(shard, *state[:6])
+
+
+def test_fused_adam_with_large_raw_segments(oracle):
+    # RAW segments long enough that the RAW kernel's XCD-aware order permutes complete rounds of
+    # tiles (8 MiB each), between and around parameter groups
+    g = torch.Generator(device=DEV)
+    g.manual_seed(31)
+    raw1 = torch.randn(5 * (1 << 20) + 3, device=DEV, generator=g)                     # 20 MiB + 12 B
+    raw2 = torch.randn(3 * (1 << 20) + 1, device=DEV, generator=g).to(torch.bfloat16)  # 6 MiB + 2 B
+    raw3 = torch.randn(2500001, device=DEV, generator=g)                               # 9.5 MiB
+    _adam_and_compare(oracle, [50000, 300001], 1 << 20, seed=12,
+                      extra_raw=[(0, raw1), (5, raw2), (10, raw3)])
+
+
+# Tuning flags of a plan change the order and the cache policy of the accesses, never the result.
+_TUNING = [ff.FF_PLAN_XCD_ORDER(1), ff.FF_PLAN_XCD_ORDER(2), ff.FF_PLAN_XCD_ORDER(3),
+           ff.FF_PLAN_XCD_ORDER(31), ff.FF_PLAN_CACHE_HINT(0),
+           ff.FF_PLAN_CACHE_HINT(1) | ff.FF_PLAN_XCD_ORDER(1), ff.FF_PLAN_CACHE_HINT(2)]
+
+
+@pytest.mark.parametrize("flags", _TUNING)
+def test_plan_tuning_flags_pack_restore(oracle, flags):
+    # 6 MiB in 32 KiB tiles: runs of 1, 2 and 4 workgroups per XCD permute several complete rounds
+    lay = wl.fragmented_layout(seed=77, n_tensors=120, mu=9.5, sigma=1.5, max_numel=1 << 18)
+    shard = wl.fragmented_shard(lay, 1 << 18, seed=flags, device=DEV)
+    assert sum(n for _, n in shard.spans) > 3 << 20
+    state = _pack_and_compare(shard, oracle, flags=flags)
+    _restore_and_compare(shard, *state[:6])
+    plan, chunks, crcs, bad, n_bad = state[:5]
+    ff.ff_restore(plan, chunks, crcs, bad, n_bad, ff.FF_RESTORE_VERIFY_ONLY)
+    torch.cuda.synchronize()
+    assert int(n_bad.item()) == 0
+
+
+@pytest.mark.parametrize("flags", _TUNING)
+def test_plan_tuning_flags_fused_step(oracle, flags):
+    # 40 and more tiles of 8192 elements: complete rounds for runs of 1, 2 and 4
+    _adam_and_compare(oracle, [200000, 77777, 5, 131072], 1 << 16, seed=flags, flags=flags)
 
 
 # ---- fp16 variant of the fused step ---------------------------------------------------------------
