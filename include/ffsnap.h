@@ -253,6 +253,27 @@ int ff_adam_step_snapshot_f16(const ff_plan *plan, const void *const *grads,
                               uint64_t *n_nonfinite, void *chunks, uint32_t *crcs,
                               void *hip_stream);
 
+/*
+ * The same step with the optimizer state kept in the snapshots themselves.  The paper holds the
+ * two most recent snapshots and alternates between them (section 4.2) and snapshots right after
+ * every update (section 6.2); here the update of step t reads the old master, m and v of every
+ * parameter group from `prev_chunks`, the snapshot of step t-1, at the segments' stream offsets,
+ * and writes the new master, m, v and 16-bit weights into `chunks`.  The plan's MASTER, M and V
+ * tensors are neither read nor written (they may be views into the snapshot buffers, or unused);
+ * the W16 tensors receive the new working weights as in the other two steps; gradients and RAW
+ * segments are read from their tensors.  Arithmetic, rounding, crcs and the zero tail are those
+ * of ff_adam_step_snapshot (bf16 plan: inv_loss_scale must be 1 and n_nonfinite NULL) or of
+ * ff_adam_step_snapshot_f16 (fp16 plan), so the result equals that step run on tensors holding
+ * the state of `prev_chunks`.  The CRCs of `prev_chunks` are not checked here (ff_restore with
+ * FF_RESTORE_VERIFY_ONLY does that).  Per element it moves 14 bytes in and 16 out, where the
+ * in-place steps move 14 in and 28 out.
+ * prev_chunks: DEVICE, 16-byte aligned, ff_plan_buffer_bytes() long, read only; it must not
+ * overlap `chunks` (FF_ERR_INVALID).
+ */
+int ff_adam_step_chained(const ff_plan *plan, const void *const *grads, const ff_adam_hparams *hp,
+                         float inv_loss_scale, uint64_t *n_nonfinite, const void *prev_chunks,
+                         void *chunks, uint32_t *crcs, void *hip_stream);
+
 /* Test helper: CRC32C of nbytes at dev_buf (DEVICE, 16-byte aligned) into *dev_out (DEVICE),
  * computed by the same tile and combine kernels as ff_pack.  Allocates and frees a small
  * scratch array, so it synchronises the stream before returning. */

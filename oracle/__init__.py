@@ -294,6 +294,31 @@ def adam_snapshot_f16(params, grads_f16, inv_scale, segments, chunk_bytes, hpara
     return buf, crcs, bad
 
 
+def adam_snapshot_chained(prev_buffer, params, grads, segments, chunk_bytes, hparams,
+                          inv_scale=None, threads=1):
+    """The step whose optimizer state lives in the snapshots (the paper alternates between its
+    two most recent snapshots, section 4.2, and snapshots right after the update, section 6.2):
+    master, m and v of every parameter group are first taken out of `prev_buffer` at their
+    segments' stream offsets (the stream is the tight concatenation of `segments`); from there on
+    it is adam_snapshot (inv_scale None: bf16) or adam_snapshot_f16.  params: (w16, master, m, v)
+    numpy arrays aliasing entries of `segments`; master, m, v are overwritten twice here (old
+    state, then new), w16 receives the new working weights.  Returns (buffer, crcs, n_nonfinite)."""
+    prev = _bytes_view(prev_buffer)
+    offset_of, off = {}, 0
+    for seg in segments:
+        offset_of[seg.__array_interface__["data"][0]] = off
+        off += seg.nbytes
+    for _, master, m, v in params:
+        for arr in (master, m, v):
+            o = offset_of[arr.__array_interface__["data"][0]]
+            _bytes_view(arr)[:] = prev[o:o + arr.nbytes]
+    if inv_scale is None:
+        buf, crcs = adam_snapshot(params, grads, segments, chunk_bytes, hparams, threads=threads)
+        return buf, crcs, 0
+    return adam_snapshot_f16(params, grads, inv_scale, segments, chunk_bytes, hparams,
+                             threads=threads)
+
+
 def razor_unique(kinds, dp_degree, distributed_optimizer):
     """Checkpoint razor (section 4.2), written out as its truth table.  kinds: 'raw', 'weight',
     'optimizer' per segment.  Returns the indices of the unique segments; the rest is redundant.

@@ -40,7 +40,7 @@ EXPORTS = ["ff_snapshot_plan", "ff_plan_destroy", "ff_plan_payload_bytes", "ff_p
            "ff_plan_buffer_bytes", "ff_plan_chunk_bytes", "ff_plan_num_segments",
            "ff_plan_num_params", "ff_plan_layout_id", "ff_plan_segment_range",
            "ff_plan_chunk_span", "ff_razor_select", "ff_pack", "ff_pack_to_host", "ff_restore", "ff_restore_chunks", "ff_adam_step_snapshot",
-           "ff_adam_step_snapshot_f16", "ff_crc32c", "ff_copy_ceiling", "ff_strerror"]
+           "ff_adam_step_snapshot_f16", "ff_adam_step_chained", "ff_crc32c", "ff_copy_ceiling", "ff_strerror"]
 
 
 class ff_segment(ctypes.Structure):
@@ -111,6 +111,10 @@ def lib():
         L.ff_adam_step_snapshot_f16.argtypes = [vp, ctypes.POINTER(vp),
                                                 ctypes.POINTER(ff_adam_hparams), ctypes.c_float,
                                                 vp, vp, vp, vp]
+        L.ff_adam_step_chained.restype = i32
+        L.ff_adam_step_chained.argtypes = [vp, ctypes.POINTER(vp),
+                                           ctypes.POINTER(ff_adam_hparams), ctypes.c_float, vp,
+                                           vp, vp, vp, vp]
         L.ff_crc32c.restype, L.ff_crc32c.argtypes = i32, [vp, u64, vp, vp]
         L.ff_copy_ceiling.restype, L.ff_copy_ceiling.argtypes = i32, [vp, vp, u64, vp]
         L.ff_strerror.restype, L.ff_strerror.argtypes = ctypes.c_char_p, [i32]
@@ -268,6 +272,19 @@ def ff_adam_step_snapshot_f16(plan, grads, hparams, inv_loss_scale, n_nonfinite,
         plan.handle, ptrs, ctypes.byref(hp), ctypes.c_float(inv_loss_scale),
         ctypes.c_void_p(n_nonfinite.data_ptr()) if n_nonfinite is not None else None,
         chunks.data_ptr(), crcs.data_ptr(), _stream_ptr(stream)))
+
+
+def ff_adam_step_chained(plan, grads, hparams, prev_chunks, chunks, crcs, inv_loss_scale=1.0,
+                         n_nonfinite=None, stream=None):
+    """The step that reads master, m, v from the snapshot `prev_chunks` and writes the new
+    snapshot into `chunks`; grads in the plan's 16-bit format."""
+    ptrs = (ctypes.c_void_p * max(len(grads), 1))(*[g.data_ptr() for g in grads])
+    hp = ff_adam_hparams(hparams["lr"], hparams["beta1"], hparams["beta2"], hparams["eps"],
+                         hparams["weight_decay"], hparams["step"])
+    _check(lib().ff_adam_step_chained(
+        plan.handle, ptrs, ctypes.byref(hp), ctypes.c_float(inv_loss_scale),
+        ctypes.c_void_p(n_nonfinite.data_ptr()) if n_nonfinite is not None else None,
+        prev_chunks.data_ptr(), chunks.data_ptr(), crcs.data_ptr(), _stream_ptr(stream)))
 
 
 def ff_crc32c(buf, nbytes, out, stream=None):

@@ -326,9 +326,10 @@ int check_restore_args(const ff_plan* p, const void* chunks, const uint32_t* crc
     return FF_OK;
 }
 
+// prev: null for the in-place step; else the snapshot that holds the old master, m and v.
 int adam_impl(const ff_plan* p, const void* const* grads, const ff_adam_hparams* hp,
-              uint32_t half_dtype, float inv_scale, uint64_t* n_nonfinite, void* chunks,
-              uint32_t* crcs, hipStream_t s)
+              uint32_t half_dtype, float inv_scale, uint64_t* n_nonfinite, const void* prev,
+              void* chunks, uint32_t* crcs, hipStream_t s)
 {
     int rc = check_device_call(p);
     if (rc != FF_OK) return rc;
@@ -338,6 +339,12 @@ int adam_impl(const ff_plan* p, const void* const* grads, const ff_adam_hparams*
     if (L.half_dtype != half_dtype) return FF_ERR_INVALID;  // bf16 plan <-> fp16 call or vice versa
     if (reinterpret_cast<uint64_t>(chunks) % 16 || reinterpret_cast<uint64_t>(crcs) % 4)
         return FF_ERR_INVALID;
+    if (prev) {
+        // the two snapshots must be different buffers: elements of `prev` are read while
+        // neighbouring ones of `chunks` are already written
+        const uint64_t a = reinterpret_cast<uint64_t>(prev), b = reinterpret_cast<uint64_t>(chunks);
+        if (a % 16 || (a < b ? b - a : a - b) < L.buffer_bytes) return FF_ERR_INVALID;
+    }
     for (size_t i = 0; i < L.params.size(); i++) {
         if (!grads[i]) return FF_ERR_NULL;
         if (reinterpret_cast<uint64_t>(grads[i]) % 2) return FF_ERR_INVALID;
@@ -359,6 +366,7 @@ int adam_impl(const ff_plan* p, const void* const* grads, const ff_adam_hparams*
     c.inv_scale = inv_scale;
     c.xcd_group = p->fused_xcd_group;
     c.n_nonfinite = n_nonfinite;
+    c.prev = static_cast<const uint8_t*>(prev);
     // The device table of gradient pointers is refreshed only when a pointer differs from the last
     // call's (a training loop passes the same buffers every step).  The array is copied into the
     // plan first: the asynchronous upload reads from there.
@@ -504,7 +512,7 @@ int ff_plan_chunk_span(const ff_plan* p, uint64_t chunk, uint64_t* first_seg, ui
 int ff_adam_step_snapshot(const ff_plan* p, const void* const* grads, const ff_adam_hparams* hp,
                           void* chunks, uint32_t* crcs, void* hip_stream)
 {
-    return adam_impl(p, grads, hp, FF_BF16, 1.0f, nullptr, chunks, crcs,
+    return adam_impl(p, grads, hp, FF_BF16, 1.0f, nullptr, nullptr, chunks, crcs,
                      static_cast<hipStream_t>(hip_stream));
 }
 
@@ -514,8 +522,21 @@ int ff_adam_step_snapshot_f16(const ff_plan* p, const void* const* grads,
                               void* hip_stream)
 {
     if (reinterpret_cast<uint64_t>(n_nonfinite) % 8) return FF_ERR_INVALID;
-    return adam_impl(p, grads, hp, FF_F16, inv_loss_scale, n_nonfinite, chunks, crcs,
+    return adam_impl(p, grads, hp, FF_F16, inv_loss_scale, n_nonfinite, nullptr, chunks, crcs,
                      static_cast<hipStream_t>(hip_stream));
+}
+
+int ff_adam_step_chained(const ff_plan* p, const void* const* grads, const ff_adam_hparams* hp,
+                         float inv_loss_scale, uint64_t* n_nonfinite, const void* prev_chunks,
+                         void* chunks, uint32_t* crcs, void* hip_stream)
+{
+    if (!p) return FF_ERR_NULL;
+    if (!prev_chunks) return FF_ERR_NULL;
+    const uint32_t half = p->layout.half_dtype;
+    if (half != FF_F16 && (inv_loss_scale != 1.0f || n_nonfinite)) return FF_ERR_INVALID;
+    if (reinterpret_cast<uint64_t>(n_nonfinite) % 8) return FF_ERR_INVALID;
+    return adam_impl(p, grads, hp, half == FF_F16 ? FF_F16 : FF_BF16, inv_loss_scale, n_nonfinite,
+                     prev_chunks, chunks, crcs, static_cast<hipStream_t>(hip_stream));
 }
 
 int ff_crc32c(const void* dev_buf, uint64_t nbytes, uint32_t* dev_out, void* hip_stream)

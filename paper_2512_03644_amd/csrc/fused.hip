@@ -159,7 +159,7 @@ __device__ __forceinline__ TileGeom tile_geom(const WorkTile& t)
 // for even and odd batches).  Registers that are never copied while a load into them is in flight,
 // and no branch between issue and use, let the compiler wait for exactly the loads a row needs,
 // while the loads of the next batch and the stores of the last one stay in flight.
-template <bool F16>
+template <bool F16, bool CHAINED>
 __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G,
                                             const uint8_t* __restrict__ grad,
                                             uint8_t* __restrict__ chunks,
@@ -175,6 +175,10 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
     uint8_t* const sp = chunks + t.soff[1];
     uint8_t* const sm = chunks + t.soff[2];
     uint8_t* const sv = chunks + t.soff[3];
+    // where the old master, m, v come from: their tensors, or the previous snapshot
+    const uint8_t* const lp = CHAINED ? C.prev + t.soff[1] : tp;
+    const uint8_t* const lm = CHAINED ? C.prev + t.soff[2] : tm;
+    const uint8_t* const lv = CHAINED ? C.prev + t.soff[3] : tv;
     const int head_lane = G.pad_el / 4, head_sub = G.pad_el % 4;  // where element 0 sits in row 0
     uint32_t nonfinite = 0;  // this lane's count of infinite or NaN gradient elements (fp16 only)
 
@@ -183,9 +187,9 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
     auto load_row = [&](int r, RowIn& in) {  // r must be a full row of the tile
         const int j0 = r * kRowElems + 4 * lane - G.pad_el;
         in.g = load8_unaligned<true>(tg + 2 * j0);
-        in.p = load16_unaligned<true>(tp + 4 * j0);
-        in.m = load16_unaligned<true>(tm + 4 * j0);
-        in.v = load16_unaligned<true>(tv + 4 * j0);
+        in.p = load16_unaligned<true>(lp + 4 * j0);
+        in.m = load16_unaligned<true>(lm + 4 * j0);
+        in.v = load16_unaligned<true>(lv + 4 * j0);
     };
 
     // copy of a row's results for the folding wavefronts
@@ -248,9 +252,11 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
         const u32x4 mo = {fm[0], fm[1], fm[2], fm[3]};
         const u32x4 vo = {fv[0], fv[1], fv[2], fv[3]};
         store8_unaligned<true>(tw + 2 * j0, w2);
-        store16_unaligned<true>(tp + 4 * j0, po);
-        store16_unaligned<true>(tm + 4 * j0, mo);
-        store16_unaligned<true>(tv + 4 * j0, vo);
+        if constexpr (!CHAINED) {
+            store16_unaligned<true>(tp + 4 * j0, po);
+            store16_unaligned<true>(tm + 4 * j0, mo);
+            store16_unaligned<true>(tv + 4 * j0, vo);
+        }
         store8_unaligned<true>(sw + 2 * j0, w2);
         store16_unaligned<true>(sp + 4 * j0, po);
         store16_unaligned<true>(sm + 4 * j0, mo);
@@ -269,15 +275,28 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
             gb[s] = 0; wb[s] = 0; p[s] = 0.f; m[s] = 0.f; v[s] = 0.f;
             if (j >= 0) {
                 gb[s] = *as_global(reinterpret_cast<const uint16_t*>(tg + 2 * j));
-                p[s] = *as_global(reinterpret_cast<const float*>(tp + 4 * j));
-                m[s] = *as_global(reinterpret_cast<const float*>(tm + 4 * j));
-                v[s] = *as_global(reinterpret_cast<const float*>(tv + 4 * j));
+                if constexpr (CHAINED) {
+                    // stream offsets of fp32 segments may be 2 mod 4: halfword loads
+                    auto f32_at = [](const uint8_t* q) {
+                        const uint16_t* h = reinterpret_cast<const uint16_t*>(q);
+                        return bits_to_f32(uint32_t(*as_global(h)) | (uint32_t(*as_global(h + 1)) << 16));
+                    };
+                    p[s] = f32_at(lp + 4 * j);
+                    m[s] = f32_at(lm + 4 * j);
+                    v[s] = f32_at(lv + 4 * j);
+                } else {
+                    p[s] = *as_global(reinterpret_cast<const float*>(tp + 4 * j));
+                    m[s] = *as_global(reinterpret_cast<const float*>(tm + 4 * j));
+                    v[s] = *as_global(reinterpret_cast<const float*>(tv + 4 * j));
+                }
                 if constexpr (F16) nonfinite += f16_nonfinite(gb[s]) ? 1u : 0u;
                 adam_element<F16>(C, gb[s], p[s], m[s], v[s], wb[s]);
                 *as_global(reinterpret_cast<uint16_t*>(tw + 2 * j)) = static_cast<uint16_t>(wb[s]);
-                *as_global(reinterpret_cast<float*>(tp + 4 * j)) = p[s];
-                *as_global(reinterpret_cast<float*>(tm + 4 * j)) = m[s];
-                *as_global(reinterpret_cast<float*>(tv + 4 * j)) = v[s];
+                if constexpr (!CHAINED) {
+                    *as_global(reinterpret_cast<float*>(tp + 4 * j)) = p[s];
+                    *as_global(reinterpret_cast<float*>(tm + 4 * j)) = m[s];
+                    *as_global(reinterpret_cast<float*>(tv + 4 * j)) = v[s];
+                }
                 *as_global(reinterpret_cast<uint16_t*>(sw + 2 * j)) = static_cast<uint16_t>(wb[s]);
                 // stream offsets of fp32 segments may be 2 mod 4: halfword stores
                 const uint32_t pb = f32_to_bits(p[s]), mb = f32_to_bits(m[s]), vb = f32_to_bits(v[s]);
@@ -470,7 +489,7 @@ __device__ __forceinline__ void run_raw_tile(const WorkTile& t, uint8_t* __restr
     if (lane == 0) add_piece(crcs, t, 0, reg);
 }
 
-template <bool F16>
+template <bool F16, bool CHAINED>
 __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
     const WorkTile* __restrict__ tiles, uint32_t n_tiles, const uint64_t* __restrict__ grads,
     const uint32_t* __restrict__ tabs, uint8_t* __restrict__ chunks, uint32_t* __restrict__ crcs,
@@ -503,7 +522,7 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
     const TileGeom G = tile_geom(t);
     if (wave < kUpdateWaves) {
         const uint8_t* grad = reinterpret_cast<const uint8_t*>(grads[t.grad_index]);
-        update_role<F16>(t, G, grad, chunks, crcs, C, buf, wave, lane);
+        update_role<F16, CHAINED>(t, G, grad, chunks, crcs, C, buf, wave, lane);
     } else {
         const int x = wave - kUpdateWaves;
         uint32_t reg;
@@ -581,13 +600,11 @@ hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_param_tiles,
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (n_param_tiles) {
-        const unsigned grid = n_param_tiles;
-        if (f16)
-            hipLaunchKernelGGL(fused_kernel<true>, dim3(grid), dim3(kWaveSize * kWavesPerBlock), 0,
-                               stream, tiles, n_param_tiles, grads, tabs, c, crcs, consts);
-        else
-            hipLaunchKernelGGL(fused_kernel<false>, dim3(grid), dim3(kWaveSize * kWavesPerBlock), 0,
-                               stream, tiles, n_param_tiles, grads, tabs, c, crcs, consts);
+        const dim3 grid(n_param_tiles), block(kWaveSize * kWavesPerBlock);
+        auto kernel = consts.prev ? (f16 ? fused_kernel<true, true> : fused_kernel<false, true>)
+                                  : (f16 ? fused_kernel<true, false> : fused_kernel<false, false>);
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, tiles, n_param_tiles, grads, tabs, c, crcs,
+                           consts);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

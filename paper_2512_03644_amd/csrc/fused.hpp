@@ -17,7 +17,10 @@ struct FusedConsts {
     AdamConsts adam;
     float inv_scale = 1.0f;            // fp16 variant: reciprocal of the loss scale
     uint64_t* n_nonfinite = nullptr;   // fp16 variant: device counter of inf/NaN gradients, or null
-    uint32_t xcd_group = 0;            // XCD-aware order of the work tiles (see kernels.hpp)
+    uint32_t xcd_group = 0;            // XCD-aware order of the work tiles (see xcd_order.h)
+    // Chained step: master, m and v are read from this snapshot buffer (at the segments' stream
+    // offsets) instead of their tensors, and those tensors are not written.  Null: in-place step.
+    const uint8_t* prev = nullptr;
 };
 
 // Device table of the fused kernels (kFusedTabWords entries): byte tables of multiplication by

@@ -604,6 +604,131 @@ def test_plan_tuning_flags_fused_step(oracle, flags):
     _adam_and_compare(oracle, [200000, 77777, 5, 131072], 1 << 16, seed=flags, flags=flags)
 
 
+# ---- the step that reads its state from the previous snapshot ------------------------------------
+
+def _chained_and_compare(oracle, numels, chunk, seed, steps=3, half=torch.bfloat16, loss_scale=1.0,
+                         extra_raw=None, flags=0):
+    """ff_adam_step_chained over `steps` steps that alternate between two snapshot buffers, against
+    the oracle's definition step by step: snapshot bytes and CRCs bit-exact (which holds the fp32
+    state to the bit, inside the 1e-6 bound), working weights exact, MASTER/M/V tensors untouched.
+    Then one more step both ways: chained, and in place on tensors restored from the snapshot."""
+    shard = wl.param_shard("a", numels, chunk, seed, DEV, with_grads=True, half=half,
+                           loss_scale=loss_scale)
+    tensors = list(shard.segments)
+    kinds, pids = [], []
+    for pid in range(len(shard.params)):
+        kinds += [ff.FF_KIND_W16, ff.FF_KIND_MASTER, ff.FF_KIND_M, ff.FF_KIND_V]
+        pids += [pid] * 4
+    for pos, t in (extra_raw or []):
+        tensors.insert(pos, t)
+        kinds.insert(pos, ff.FF_KIND_RAW)
+        pids.insert(pos, 0)
+    plan = ff.ff_snapshot_plan(tensors, chunk, flags=flags, kinds=kinds, param_ids=pids)
+    host = [wl.to_numpy_bytes(t) for t in tensors]
+    views = {id(t): h for t, h in zip(tensors, host)}
+    params_np, grads_np = [], []
+    for p in shard.params:
+        params_np.append((views[id(p.w16)].view(np.uint16), views[id(p.master)].view(np.float32),
+                          views[id(p.m)].view(np.float32), views[id(p.v)].view(np.float32)))
+        grads_np.append(wl.to_numpy_bytes(p.grad).view(np.uint16))
+    grads = [p.grad for p in shard.params]
+    bufs = [ff.alloc_outputs(plan, DEV)[:2] for _ in range(2)]
+    ff.ff_pack(plan, *bufs[0])                     # snapshot 0: the initial state
+    torch.cuda.synchronize()
+    prev_np, prev_crcs = oracle.pack(host, chunk, threads=8)
+    assert np.array_equal(bufs[0][0].cpu().numpy(), prev_np)
+    # from here on the optimizer state lives in the snapshots: the tensors hold poison
+    for p in shard.params:
+        for t in (p.master, p.m, p.v):
+            t.view(torch.int32).fill_(0x7FC00BAD)
+    f16 = half == torch.float16
+    inv = float(np.float32(1.0 / loss_scale)) if f16 else 1.0
+    n_nonfinite = torch.full((1,), -1, dtype=torch.int64, device=DEV) if f16 else None
+    for k in range(steps):
+        hp = dict(HP, step=HP["step"] + k)
+        src, (dst, dst_crcs) = bufs[k % 2][0], bufs[(k + 1) % 2]
+        dst.fill_(0xA5)
+        dst_crcs.fill_(-1)
+        ff.ff_adam_step_chained(plan, grads, hp, src, dst, dst_crcs, inv, n_nonfinite)
+        torch.cuda.synchronize()
+        want_buf, want_crcs, want_bad = oracle.adam_snapshot_chained(
+            prev_np, params_np, grads_np, host, chunk, hp, inv_scale=inv if f16 else None, threads=8)
+        assert np.array_equal(dst.cpu().numpy(), want_buf), k
+        assert np.array_equal(_u32(dst_crcs), want_crcs), k
+        if f16:
+            assert int(n_nonfinite.item()) == want_bad == 0
+        for p, (w16, _, _, _) in zip(shard.params, params_np):
+            assert np.array_equal(wl.to_numpy_bytes(p.w16).view(np.uint16), w16)
+            for t in (p.master, p.m, p.v):
+                assert bool((t.view(torch.int32) == 0x7FC00BAD).all())
+        prev_np = want_buf
+    # the chain equals the in-place step: load the last snapshot into the tensors and step both ways
+    last, (other, other_crcs) = bufs[steps % 2], bufs[(steps + 1) % 2]
+    _, _, bad, n_bad = ff.alloc_outputs(plan, DEV)
+    hp = dict(HP, step=HP["step"] + steps)
+    ff.ff_adam_step_chained(plan, grads, hp, last[0], other, other_crcs, inv, n_nonfinite)
+    torch.cuda.synchronize()
+    chained_buf, chained_crcs = other.cpu().numpy().copy(), _u32(other_crcs).copy()
+    ff.ff_restore(plan, last[0], last[1], bad, n_bad)
+    torch.cuda.synchronize()
+    assert int(n_bad.item()) == 0
+    if f16:
+        ff.ff_adam_step_snapshot_f16(plan, grads, hp, inv, n_nonfinite, other, other_crcs)
+    else:
+        ff.ff_adam_step_snapshot(plan, grads, hp, other, other_crcs)
+    torch.cuda.synchronize()
+    assert np.array_equal(other.cpu().numpy(), chained_buf)
+    assert np.array_equal(_u32(other_crcs), chained_crcs)
+
+
+@pytest.mark.parametrize("chunk", [1024, 4096, 1 << 16, 1 << 20])
+def test_chained_step_small_ragged(oracle, chunk):
+    numels = [1, 3, 255, 256, 257, 1000, 4097, 70001, 131072, 65536 + 255, 5, 77]
+    _chained_and_compare(oracle, numels, chunk, seed=chunk + 2)
+
+
+def test_chained_step_with_raw_segments_and_tuning_flags(oracle):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(5)
+    raw1 = torch.randn(3001, device=DEV, generator=g)
+    raw2 = torch.randn(70001, device=DEV, generator=g).to(torch.bfloat16)  # fp32 streams at 2 mod 4
+    raw3 = torch.randn(9, device=DEV, generator=g).to(torch.bfloat16)
+    _chained_and_compare(oracle, [1000, 33333, 77, 200000], 4096, seed=19,
+                         extra_raw=[(0, raw1), (5, raw2), (14, raw3)],
+                         flags=ff.FF_PLAN_XCD_ORDER(1))
+
+
+@pytest.mark.parametrize("loss_scale", [1.0, 4096.0])
+def test_chained_step_f16(oracle, loss_scale):
+    _chained_and_compare(oracle, [5000, 12345, 300, 3], 4096, seed=23, half=torch.float16,
+                         loss_scale=loss_scale)
+
+
+def test_chained_step_argument_errors():
+    shard = wl.param_shard("a", [5000], 4096, 5, DEV, with_grads=True)
+    plan = ff.plan_for_shard(shard)
+    a, crcs, _, _ = ff.alloc_outputs(plan, DEV)
+    both = torch.zeros(2 * a.numel() + 64, dtype=torch.uint8, device=DEV)
+    grads = [shard.params[0].grad]
+    n_nonfinite = torch.zeros(1, dtype=torch.int64, device=DEV)
+    n = a.numel()
+    cases = [
+        lambda: ff.ff_adam_step_chained(plan, grads, HP, a, a, crcs),                        # the same buffer
+        lambda: ff.ff_adam_step_chained(plan, grads, HP, both[16:16 + n], both[:n], crcs),   # overlapping
+        lambda: ff.ff_adam_step_chained(plan, grads, HP, both[n - 16:2 * n - 16], both[:n], crcs),
+        lambda: ff.ff_adam_step_chained(plan, grads, HP, both[n + 8:2 * n + 8], both[:n], crcs),  # misaligned
+        lambda: ff.ff_adam_step_chained(plan, grads, HP, both[n:2 * n], both[:n], crcs, 0.5),     # bf16 plan
+        lambda: ff.ff_adam_step_chained(plan, grads, HP, both[n:2 * n], both[:n], crcs, 1.0, n_nonfinite),
+        lambda: ff.ff_adam_step_chained(plan, grads, dict(HP, step=0), both[n:2 * n], both[:n], crcs),
+    ]
+    for case in cases:
+        with pytest.raises(ff.FFError) as e:
+            case()
+        assert e.value.status == ff.FF_ERR_INVALID
+    ff.ff_adam_step_chained(plan, grads, HP, both[n:2 * n], both[:n], crcs)   # adjacent buffers are fine
+    torch.cuda.synchronize()
+
+
 # ---- fp16 variant of the fused step ---------------------------------------------------------------
 
 @pytest.mark.parametrize("chunk,loss_scale", [(1024, 1.0), (4096, 1024.0), (1 << 16, 65536.0),

@@ -276,3 +276,114 @@ def test_f16_step_counts_nonfinite_gradients(oracle):
     ok[[5, 17, 900]] = False
     assert np.isfinite(p[ok]).all() and np.isfinite(a[ok]).all() and np.isfinite(b[ok]).all()
     assert not np.isfinite(a[5]) and not np.isfinite(a[17]) and np.isnan(a[900])
+
+
+# ---- the step that reads its state from the previous snapshot ------------------------------------
+
+def _chained_case(seed, numels, half=torch.bfloat16):
+    """Parameter groups with a RAW segment in between, the previous state as its own arrays, and
+    the previous snapshot built with numpy alone (tight concatenation, zero fill)."""
+    rng = np.random.default_rng(seed)
+    segs, params, grads, prev_state = [], [], [], []
+    for k, n in enumerate(numels):
+        master, m, v, g16 = _draw(n, seed + k)
+        w_old = _bits(torch.from_numpy(master).to(half))
+        prev_state.append((w_old, master, m, v))
+        # what the step is given: arrays of the right sizes holding garbage it must not use
+        grp = (np.full(n, 0x7FC1, np.uint16), np.full(n, np.nan, np.float32),
+               np.full(n, np.nan, np.float32), np.full(n, np.nan, np.float32))
+        params.append(grp)
+        segs += list(grp)
+        grads.append(_bits(g16.to(torch.float32).to(half)))
+        if k == 0:
+            segs.append(rng.integers(0, 256, 333 * 2, dtype=np.uint8))  # a RAW segment
+    return segs, params, grads, prev_state
+
+
+def _numpy_buffer(arrays, chunk):
+    stream = np.concatenate([np.ascontiguousarray(a).view(np.uint8).reshape(-1) for a in arrays])
+    n_chunks = -(-stream.size // chunk)
+    buf = np.zeros(n_chunks * chunk, np.uint8)
+    buf[:stream.size] = stream
+    return buf
+
+
+def test_chained_step_takes_its_state_from_the_previous_snapshot(oracle):
+    chunk, numels = 4096, [1000, 3, 4099]
+    segs, params, grads, prev_state = _chained_case(7, numels)
+    raw = segs[4]
+    prev_list = []
+    for k, grp in enumerate(prev_state):
+        prev_list += list(grp)
+        if k == 0:
+            prev_list.append(np.zeros_like(raw))  # the RAW bytes of the old snapshot are not used
+    prev = _numpy_buffer(prev_list, chunk)
+    buf, crcs, bad = oracle.adam_snapshot_chained(prev, params, grads, segs, chunk, HP)
+    assert bad == 0
+    # expected: the pinned single-tensor step on the old state, laid out with numpy alone
+    want = []
+    for k, ((w, master, m, v), g) in enumerate(zip(prev_state, grads)):
+        master, m, v, w = master.copy(), m.copy(), v.copy(), w.copy()
+        oracle.adam_f32(g, master, m, v, w, **HP)
+        want += [w, master, m, v]
+        if k == 0:
+            want.append(raw)
+        assert np.array_equal(params[k][0], w)          # the new working weights are handed back
+    want_buf = _numpy_buffer(want, chunk)
+    assert np.array_equal(buf, want_buf)
+    assert [int(c) for c in crcs] == [oracle.crc32c_bitwise(want_buf[i:i + chunk])
+                                      for i in range(0, want_buf.size, chunk)]
+
+
+def test_chained_step_closed_form(oracle):
+    # g = 0, lr = 0, wd = 0: master' = master, m' = fl(b1 m), v' = fl(b2 v), w' = bf16(master);
+    # distinct m and v at distinct offsets, so a stream read from the wrong place shows
+    chunk, numels = 1024, [777, 130]
+    segs, params, grads, prev_state = _chained_case(11, numels)
+    grads = [np.zeros_like(g) for g in grads]
+    hp = dict(HP, lr=0.0, weight_decay=0.0)
+    prev_list = []
+    for k, grp in enumerate(prev_state):
+        prev_list += list(grp)
+        if k == 0:
+            prev_list.append(segs[4])
+    prev = _numpy_buffer(prev_list, chunk)
+    buf, crcs, _ = oracle.adam_snapshot_chained(prev, params, grads, segs, chunk, hp)
+    b1, b2 = np.float32(hp["beta1"]), np.float32(hp["beta2"])
+    off = 0
+    for k, (w_old, master, m, v) in enumerate(prev_state):
+        n = master.size
+        got_w = buf[off:off + 2 * n].view(np.uint16); off += 2 * n
+        got_p = buf[off:off + 4 * n].view(np.float32); off += 4 * n
+        got_m = buf[off:off + 4 * n].view(np.float32); off += 4 * n
+        got_v = buf[off:off + 4 * n].view(np.float32); off += 4 * n
+        if k == 0:
+            off += segs[4].size
+        assert np.array_equal(got_p, master)
+        assert np.array_equal(got_m, b1 * m)
+        assert np.array_equal(got_v, b2 * v)
+        assert np.array_equal(got_w, _bits(torch.from_numpy(master).to(torch.bfloat16)))
+
+
+def test_chained_fp16_step_counts_and_scales(oracle):
+    chunk, numels = 2048, [515, 64]
+    segs, params, grads, prev_state = _chained_case(13, numels, half=torch.float16)
+    grads[0][5] = 0x7C00  # +inf
+    grads[1][7] = 0x7E00  # NaN
+    prev_list = []
+    for k, grp in enumerate(prev_state):
+        prev_list += list(grp)
+        if k == 0:
+            prev_list.append(segs[4])
+    prev = _numpy_buffer(prev_list, chunk)
+    inv = float(np.float32(1.0 / 512.0))
+    buf, crcs, bad = oracle.adam_snapshot_chained(prev, params, grads, segs, chunk, HP, inv_scale=inv)
+    assert bad == 2
+    want = []
+    for k, ((w, master, m, v), g) in enumerate(zip(prev_state, grads)):
+        master, m, v, w = master.copy(), m.copy(), v.copy(), w.copy()
+        oracle.adam_f32_f16(g, inv, master, m, v, w, **HP)
+        want += [w, master, m, v]
+        if k == 0:
+            want.append(segs[4])
+    assert np.array_equal(buf, _numpy_buffer(want, chunk))
