@@ -254,6 +254,28 @@ def main():
     extra = {"verify_only": {"avg_ms": round(verify_ms, 4),
                              "payload_GBps": round(N / verify_ms / 1e6, 1),
                              "frac_of_peak": round(N / verify_ms / 1e6 / HBM_PEAK_GBS, 4)}}
+    if with_adam:
+        # The fused step with the optimizer state kept in the two alternating snapshots (reads
+        # 14 B and writes 16 B per element): reported beside the step, not part of it.  It runs
+        # last, from the step's final snapshot, since it moves the state out of the tensors.
+        ff.ff_pack(plan, chunks, crcs)     # the copy-ceiling run above overwrote the buffer
+        chunks2 = torch.empty_like(chunks)
+        crcs2 = torch.empty_like(crcs)
+        pair = [(chunks, crcs), (chunks2, crcs2)]
+
+        def op_chained():
+            ff.ff_adam_step_chained(plan, grads, hp, pair[0][0], pair[1][0], pair[1][1])
+            pair.reverse()
+        ts = event_ms(op_chained, 6, torch)
+        chained_ms = sum(ts) / len(ts)
+        ff.ff_restore(plan, pair[0][0], pair[0][1], bad, n_bad, flags=ff.FF_RESTORE_VERIFY_ONLY)
+        torch.cuda.synchronize()
+        assert int(n_bad.item()) == 0
+        extra["adam_chained"] = {"avg_ms": round(chained_ms, 4), "min_ms": round(min(ts), 4),
+                                 "bytes_per_launch": 30 * n_el,
+                                 "traffic_GBps": round(30 * n_el / chained_ms / 1e6, 1),
+                                 "frac_of_peak": round(30 * n_el / chained_ms / 1e6 / HBM_PEAK_GBS, 4)}
+        del chunks2
     metric = "snapshot pack+CRC and restore GB/s, % of HBM peak, 7B-shaped shard"
     if args.workload != "llama7b":
         metric = "snapshot pack+CRC and restore GB/s, %% of HBM peak, %s shard" % args.workload

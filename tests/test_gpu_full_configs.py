@@ -182,6 +182,53 @@ def test_config4_fused_adam_full_fp16(oracle):
     assert torch.equal(chunks, chunks2)
 
 
+def test_config4_chained_step_full(oracle):
+    """Config 4 with the optimizer state kept in the snapshots: the step reads snapshot A and writes
+    snapshot B.  Sampled parameter groups against the oracle, the tensors it must not touch, and
+    B == the in-place step run on tensors loaded from A."""
+    shard = wl.config_llama7b(DEV, with_grads=True)
+    plan = ff.plan_for_shard(shard)
+    hp = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1000)
+    grads = [p.grad for p in shard.params]
+    a, crcs_a, bad, n_bad = ff.alloc_outputs(plan, DEV)
+    b, crcs_b, _, _ = ff.alloc_outputs(plan, DEV)
+    ff.ff_pack(plan, a, crcs_a)
+    sample = [0, 1, 5, 7, 100, 224, 225]
+    host = {}
+    for i in sample:
+        p = shard.params[i]
+        host[i] = [wl.to_numpy_bytes(t) for t in (p.w16, p.master, p.m, p.v, p.grad)]
+    for p in shard.params:
+        for t in (p.master, p.m, p.v):
+            t.view(torch.int32).fill_(0x7FC00BAD)
+    b.fill_(0xA5)
+    ff.ff_adam_step_chained(plan, grads, hp, a, b, crcs_b)
+    torch.cuda.synchronize()
+    for i in sample:
+        w16, master, m, v, g = host[i]
+        oracle.adam_f32(g.view(np.uint16), master.view(np.float32), m.view(np.float32),
+                        v.view(np.float32), w16.view(np.uint16), **hp)
+        p = shard.params[i]
+        assert np.array_equal(wl.to_numpy_bytes(p.w16), w16), i
+        for k, want in enumerate((w16, master, m, v)):
+            lo, hi = plan.segment_range(4 * i + k)
+            assert np.array_equal(b[lo:hi].cpu().numpy(), want), (i, k)
+        for t in (p.master, p.m, p.v):
+            assert bool((t.view(torch.int32) == 0x7FC00BAD).all()), i
+    # the same step in place, on tensors loaded from snapshot A
+    ff.ff_restore(plan, a, crcs_a, bad, n_bad)
+    torch.cuda.synchronize()
+    assert int(n_bad.item()) == 0
+    c, crcs_c = a, crcs_a                      # A is no longer needed: reuse its memory
+    ff.ff_adam_step_snapshot(plan, grads, hp, c, crcs_c)
+    torch.cuda.synchronize()
+    assert torch.equal(crcs_b, crcs_c)
+    assert torch.equal(b, c)
+    rng = np.random.default_rng(14)
+    _check_sampled_chunks(oracle, plan, shard.segments, b, crcs_b,
+                          _sample(plan, len(shard.segments), rng, k=8))
+
+
 def test_config5_llama70b_verified_restore(oracle):
     shard = wl.config_llama70b(DEV)
     plan = ff.plan_for_shard(shard)

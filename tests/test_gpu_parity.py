@@ -528,6 +528,51 @@ def test_hip_graph_replays_of_the_whole_step():
         assert int(n_bad.item()) == 0 and torch.equal(chunks, pk) and torch.equal(crcs, pcrcs)
 
 
+def test_hip_graph_replays_of_two_chained_steps():
+    """Two chained steps, A -> B -> A, captured as one graph: every replay advances the state in
+    the snapshots by two steps and must equal the same two steps taken eagerly."""
+    numels = [3000, 70001, 255, 40000]
+    shard = wl.param_shard("a", numels, 1 << 16, 35, DEV, with_grads=True)
+    plan = ff.plan_for_shard(shard)
+    grads = [p.grad for p in shard.params]
+    a, crcs_a, bad, n_bad = ff.alloc_outputs(plan, DEV)
+    b, crcs_b, _, _ = ff.alloc_outputs(plan, DEV)
+    ff.ff_pack(plan, a, crcs_a)
+
+    def two_steps():
+        ff.ff_adam_step_chained(plan, grads, HP, a, b, crcs_b)
+        ff.ff_adam_step_chained(plan, grads, HP, b, a, crcs_a)
+
+    start = a.clone()
+    two_steps()                                      # eager once: uploads the pointer table
+    torch.cuda.synchronize()
+    a.copy_(start)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        two_steps()
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(6)
+    for rep in range(3):
+        start = a.clone()
+        for t in grads:                              # eager work between the replays
+            t.copy_(torch.randn(t.numel(), device=DEV, generator=gen).mul_(1e-3))
+        b.fill_(0xA5)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [x.clone() for x in (a, crcs_a, b, crcs_b)] + [p.w16.clone() for p in shard.params]
+        a.copy_(start)
+        b.fill_(0xA5)
+        two_steps()
+        torch.cuda.synchronize()
+        want = [a, crcs_a, b, crcs_b] + [p.w16 for p in shard.params]
+        for x, y in zip(got, want):
+            assert torch.equal(x.view(torch.uint8), y.view(torch.uint8)), rep
+        assert not torch.equal(a, start)
+        ff.ff_restore(plan, a, crcs_a, bad, n_bad, ff.FF_RESTORE_VERIFY_ONLY)
+        torch.cuda.synchronize()
+        assert int(n_bad.item()) == 0
+
+
 @pytest.mark.parametrize("seed", list(range(10)))
 def test_fused_adam_random_cases(oracle, seed):
     """Seeded random shapes: group sizes from one element to a few tiles, any chunk size, RAW
@@ -551,6 +596,10 @@ def test_fused_adam_random_cases(oracle, seed):
               eps=1e-8, weight_decay=float(rng.choice([0.0, 0.1])), step=int(rng.integers(1, 2000)))
     _adam_and_compare(oracle, numels, chunk, seed=2000 + seed, hp=hp, extra_raw=extra or None,
                       half=half, loss_scale=1024.0 if seed % 2 else 1.0)
+    if seed < 6:  # the same shapes with the state kept in the snapshots
+        _chained_and_compare(oracle, numels, chunk, seed=2500 + seed, steps=2,
+                             extra_raw=extra or None, half=half,
+                             loss_scale=1024.0 if seed % 2 else 1.0)
 
 
 @pytest.mark.parametrize("seed", list(range(8)))

@@ -102,6 +102,15 @@ def test_host_only_plan_refuses_device_work():
     assert L.ff_pack(plan.handle, dummy, dummy, None) == ff.FF_ERR_HOST_ONLY
     assert L.ff_restore(plan.handle, dummy, dummy, dummy, dummy, 0, None) == ff.FF_ERR_HOST_ONLY
     assert L.ff_pack(None, dummy, dummy, None) == ff.FF_ERR_NULL
+    hp = ff.ff_adam_hparams(3e-4, 0.9, 0.95, 1e-8, 0.1, 1)
+    ptrs = (ctypes.c_void_p * 1)(16)
+    other = ctypes.c_void_p(1 << 40)
+    assert L.ff_adam_step_chained(plan.handle, ptrs, ctypes.byref(hp), ctypes.c_float(1.0), None,
+                                  other, dummy, dummy, None) == ff.FF_ERR_HOST_ONLY
+    assert L.ff_adam_step_chained(None, ptrs, ctypes.byref(hp), ctypes.c_float(1.0), None,
+                                  other, dummy, dummy, None) == ff.FF_ERR_NULL
+    assert L.ff_adam_step_chained(plan.handle, ptrs, ctypes.byref(hp), ctypes.c_float(1.0), None,
+                                  None, dummy, dummy, None) == ff.FF_ERR_NULL
     assert L.ff_plan_segment_range(plan.handle, 5, ctypes.byref(ctypes.c_uint64()),
                                    ctypes.byref(ctypes.c_uint64())) == ff.FF_ERR_INVALID
 
