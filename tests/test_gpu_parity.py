@@ -301,6 +301,28 @@ def test_pack_on_a_side_stream(oracle):
     assert np.array_equal(_u32(crcs), want_crcs) and int(n_bad.item()) == 0
 
 
+def test_two_plans_on_two_streams_at_once(oracle):
+    """One plan per stream is the rule for work that overlaps in time: two shards packed and
+    verified concurrently, each through its own plan, stream and buffers, several times over."""
+    shards = [wl.param_shard("s%d" % k, [300000 + 7 * k, 70001, 333], 1 << 18, 40 + k, DEV,
+                             tiny_recipe=True) for k in range(2)]
+    plans = [ff.plan_for_shard(s) for s in shards]
+    outs = [ff.alloc_outputs(p, DEV) for p in plans]
+    streams = [torch.cuda.Stream() for _ in plans]
+    for st in streams:
+        st.wait_stream(torch.cuda.current_stream())
+    for _ in range(5):
+        for plan, (chunks, crcs, bad, n_bad), st in zip(plans, outs, streams):
+            ff.ff_pack(plan, chunks, crcs, stream=st)
+            ff.ff_restore(plan, chunks, crcs, bad, n_bad, flags=ff.FF_RESTORE_VERIFY_ONLY, stream=st)
+    for st in streams:
+        st.synchronize()
+    for shard, (chunks, crcs, bad, n_bad) in zip(shards, outs):
+        want_buf, want_crcs = oracle.pack(_host_segments(shard)[0], shard.chunk_bytes, threads=8)
+        assert np.array_equal(chunks.cpu().numpy(), want_buf)
+        assert np.array_equal(_u32(crcs), want_crcs) and int(n_bad.item()) == 0
+
+
 # ---- fused AdamW step + snapshot -----------------------------------------------------------------
 
 HP = dict(lr=3e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1000)
