@@ -279,8 +279,9 @@ int ff_adam_step_chained(const ff_plan *plan, const void *const *grads, const ff
  * scratch array, so it synchronises the stream before returning. */
 int ff_crc32c(const void *dev_buf, uint64_t nbytes, uint32_t *dev_out, void *hip_stream);
 
-/* Bench helper: plain 16-byte-per-lane device copy of nbytes (both DEVICE, 16-byte aligned,
- * nbytes a multiple of 16): the measured bandwidth ceiling printed beside the real kernels. */
+/* Bench helper: plain device copy of nbytes (both DEVICE, 16-byte aligned, nbytes a multiple of
+ * 16, the ranges disjoint) in the access pattern of ff_pack but without the CRC: the measured
+ * bandwidth ceiling printed beside the real kernels. */
 int ff_copy_ceiling(void *dst, const void *src, uint64_t nbytes, void *hip_stream);
 
 /* Static string for a status code; for FF_ERR_HIP the text of the last HIP error seen by the

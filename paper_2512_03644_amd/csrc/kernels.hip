@@ -578,13 +578,36 @@ __global__ void finish_crc_kernel(const uint32_t* __restrict__ partial, uint32_t
 
 __global__ void zero_u64_kernel(uint64_t* p) { *p = 0; }
 
-__global__ __launch_bounds__(256) void copy_kernel(u32x4* __restrict__ dst,
-                                                   const u32x4* __restrict__ src, uint64_t n16)
+// Plain copy in the tile kernel's access pattern, without the CRC: 32 KiB per wavefront with 16
+// rows in flight, 4 wavefronts per workgroup on adjacent tiles, XCD-aware order.  The reference
+// that pack and restore are measured against.  n16 counts 16-byte units.
+constexpr int kCopyRows = 32, kCopyDepth = 16;
+__global__ __launch_bounds__(kWaveSize * kWavesPerBlock) void copy_kernel(
+    u32x4* __restrict__ dst, const u32x4* __restrict__ src, uint64_t n16)
 {
-    const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
-    for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n16;
-         i += stride)
-        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+    const uint32_t lane = threadIdx.x & (kWaveSize - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
+    const uint64_t tile = uint64_t(xcd_order(blockIdx.x, gridDim.x, 8)) * kWavesPerBlock + wave;
+    const uint64_t i0 = tile * (kCopyRows * kWaveSize);
+    if (i0 >= n16) return;
+    if (i0 + kCopyRows * kWaveSize <= n16) {
+        const u32x4* const s = src + i0 + lane;
+        u32x4* const d = dst + i0 + lane;
+        u32x4 w[kCopyDepth];
+        static_for<kCopyDepth>([&](auto k) { w[k] = __builtin_nontemporal_load(s + k * kWaveSize); });
+        static_for<kCopyRows>([&](auto Jc) {
+            constexpr int J = Jc;
+            __builtin_nontemporal_store(w[J % kCopyDepth], d + J * kWaveSize);
+            if constexpr (J + kCopyDepth < kCopyRows) {
+                __builtin_amdgcn_sched_barrier(0);
+                w[J % kCopyDepth] = __builtin_nontemporal_load(s + (J + kCopyDepth) * kWaveSize);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+    } else {
+        for (uint64_t i = i0 + lane; i < n16; i += kWaveSize)
+            __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+    }
 }
 
 }  // namespace
@@ -674,10 +697,12 @@ hipError_t launch_copy(void* dst, const void* src, uint64_t nbytes, hipStream_t 
 {
     const uint64_t n16 = nbytes / 16;
     if (n16 == 0) return hipSuccess;
-    uint64_t blocks = (n16 + 255) / 256;
-    if (blocks > 256 * 32) blocks = 256 * 32;
-    hipLaunchKernelGGL(copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream,
-                       static_cast<u32x4*>(dst), static_cast<const u32x4*>(src), n16);
+    const uint64_t tiles = (n16 + kCopyRows * kWaveSize - 1) / (kCopyRows * kWaveSize);
+    const uint64_t blocks = (tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(copy_kernel, dim3(static_cast<unsigned>(blocks)),
+                       dim3(kWaveSize * kWavesPerBlock), 0, stream, static_cast<u32x4*>(dst),
+                       static_cast<const u32x4*>(src), n16);
     return hipGetLastError();
 }
 

@@ -301,6 +301,21 @@ def test_pack_on_a_side_stream(oracle):
     assert np.array_equal(_u32(crcs), want_crcs) and int(n_bad.item()) == 0
 
 
+@pytest.mark.parametrize("nbytes", [0, 16, 1024, 32768 - 16, 32768, 32768 + 16, 5 * 32768 + 4096,
+                                    64 * 4 * 32768, 3 * 64 * 4 * 32768 + 7 * 32768 + 48])
+def test_copy_ceiling_copies_exactly(nbytes):
+    # the bench's reference copy: whole tiles, a ragged last tile, several XCD rounds; the bytes
+    # around the destination range stay as they were
+    g = torch.Generator(device=DEV)
+    g.manual_seed(nbytes + 1)
+    src = torch.randint(0, 256, (nbytes + 64,), dtype=torch.uint8, device=DEV, generator=g)
+    dst = torch.full((nbytes + 128,), 0xA5, dtype=torch.uint8, device=DEV)
+    ff.ff_copy_ceiling(dst[64:], src, nbytes)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[64:64 + nbytes], src[:nbytes])
+    assert bool((dst[:64] == 0xA5).all()) and bool((dst[64 + nbytes:] == 0xA5).all())
+
+
 def test_two_plans_on_two_streams_at_once(oracle):
     """One plan per stream is the rule for work that overlaps in time: two shards packed and
     verified concurrently, each through its own plan, stream and buffers, several times over."""
