@@ -81,7 +81,8 @@ int upload_tables(ff_plan* p)
     const uint64_t o_ftabs = align_up(o_grads + L.params.size() * 8, 256);
     const uint64_t o_selt = align_up(o_ftabs + kFusedTabWords * 4, 256);
     const uint64_t o_selc = align_up(o_selt + L.n_tiles * 4, 256);
-    const uint64_t total = align_up(o_selc + L.n_chunks * 4, 256);
+    const uint64_t o_tbase = align_up(o_selc + L.n_chunks * 4, 256);
+    const uint64_t total = align_up(o_tbase + L.n_tiles * 8, 256);
 
     std::vector<unsigned char> host(total, 0);
     uint64_t* h_off = reinterpret_cast<uint64_t*>(host.data() + o_off);
@@ -92,6 +93,7 @@ int upload_tables(ff_plan* p)
     }
     h_off[n] = L.payload;
     std::memcpy(host.data() + o_first, L.tile_first_seg.data(), L.n_tiles * 4);
+    std::memcpy(host.data() + o_tbase, L.tile_base.data(), L.n_tiles * 8);
     build_tab_u(reinterpret_cast<uint32_t*>(host.data() + o_tab));
     if (!work.empty()) std::memcpy(host.data() + o_work, work.data(), work.size() * sizeof(WorkTile));
     build_fused_tabs(reinterpret_cast<uint32_t*>(host.data() + o_ftabs));
@@ -107,6 +109,7 @@ int upload_tables(ff_plan* p)
     t.seg_off = reinterpret_cast<const uint64_t*>(d + o_off);
     t.seg_ptr = reinterpret_cast<const uint64_t*>(d + o_ptr);
     t.tile_first_seg = reinterpret_cast<const uint32_t*>(d + o_first);
+    t.tile_base = reinterpret_cast<const uint64_t*>(d + o_tbase);
     t.tab_u = reinterpret_cast<const uint32_t*>(d + o_tab);
     t.partial = reinterpret_cast<uint32_t*>(d + o_partial);
     p->work = reinterpret_cast<const WorkTile*>(d + o_work);

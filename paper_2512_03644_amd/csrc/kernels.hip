@@ -206,6 +206,49 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
     constexpr bool kSegNT = (HINT & 1) != 0;  // non-temporal accesses on the tensor side
     constexpr bool kBufNT = (HINT & 2) != 0;  // non-temporal accesses on the chunk-buffer side
 
+    uint32_t S[kNE][kNF];
+    static_for<kNE>([&](auto e) { static_for<kNF>([&](auto f) { S[e][f] = 0; }); });
+
+    // Whole-tile paths: all rows real and, on the tensor side, inside one segment.
+    auto whole_tile = [&](auto rows_c, auto depth_c, const uint8_t* bp, const uint8_t* tp) {
+        constexpr int kRows = rows_c, kD = depth_c;
+        static_assert(kRows % kNE == 0 && kD <= kRows, "whole-tile path");
+        auto fetch = [&](int r) {
+            return (MODE == kPack) ? load16_unaligned<kSegNT>(tp + r * kRowBytes)
+                                   : load16_stream<kBufNT>(bp + r * kRowBytes);
+        };
+        u32x4 w[kD];
+        static_for<kD>([&](auto k) { w[k] = fetch(k); });
+        static_for<kRows>([&](auto Jc) {
+            constexpr int J = Jc;
+            const u32x4 x = w[J % kD];
+            if (MODE == kPack) store16_stream<kBufNT>(const_cast<uint8_t*>(bp) + J * kRowBytes, x);
+            if (MODE == kRestore)
+                store16_unaligned<kSegNT>(const_cast<uint8_t*>(tp) + J * kRowBytes, x);
+            fold_word<J % kNE>(S, x);
+            if constexpr (J + kD < kRows) {
+                __builtin_amdgcn_sched_barrier(0);
+                w[J % kD] = fetch(J + kD);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+        const uint32_t reg = reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]);
+        if (lane == 0) partial[tile] = reg;
+    };
+    // Pack: a default-size tile that the plan found inside one segment starts after a single
+    // table read; the segment tables are walked only for the other tiles.  (Restore, whose loads
+    // do not wait for a tensor address, measured 1 % slower that way and keeps the walk.)
+    if (MODE == kPack && T.tile_base && T.tile_rows == kWholeRows &&
+        R == static_cast<int>(T.tile_rows)) {
+        const uint64_t tb = T.tile_base[tile];
+        if (tb) {
+            whole_tile(std::integral_constant<int, kWholeRows>{},
+                       std::integral_constant<int, kWholeDepth<MODE>>{}, chunks + s_base + lane16,
+                       reinterpret_cast<const uint8_t*>(tb) + lane16);
+            return;
+        }
+    }
+
     Cursor cin, cout;  // pack reads through cin; restore writes through cout
     if (MODE == kPack) cursor_init(cin, seg_off, seg_ptr, tile_first_seg[tile]);
     if (MODE == kRestore) cursor_init(cout, seg_off, seg_ptr, tile_first_seg[tile]);
@@ -249,41 +292,11 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
         return true;
     };
 
-    uint32_t S[kNE][kNF];
-    static_for<kNE>([&](auto e) { static_for<kNF>([&](auto f) { S[e][f] = 0; }); });
-
-    // Whole-tile paths: all rows real and, on the tensor side, inside one segment.
-    auto whole_tile = [&](auto rows_c, auto depth_c, const uint8_t* bp, const uint8_t* tp) {
-        constexpr int kRows = rows_c, kD = depth_c;
-        static_assert(kRows % kNE == 0 && kD <= kRows, "whole-tile path");
-        auto fetch = [&](int r) {
-            return (MODE == kPack) ? load16_unaligned<kSegNT>(tp + r * kRowBytes)
-                                   : load16_stream<kBufNT>(bp + r * kRowBytes);
-        };
-        u32x4 w[kD];
-        static_for<kD>([&](auto k) { w[k] = fetch(k); });
-        static_for<kRows>([&](auto Jc) {
-            constexpr int J = Jc;
-            const u32x4 x = w[J % kD];
-            if (MODE == kPack) store16_stream<kBufNT>(const_cast<uint8_t*>(bp) + J * kRowBytes, x);
-            if (MODE == kRestore)
-                store16_unaligned<kSegNT>(const_cast<uint8_t*>(tp) + J * kRowBytes, x);
-            fold_word<J % kNE>(S, x);
-            if constexpr (J + kD < kRows) {
-                __builtin_amdgcn_sched_barrier(0);
-                w[J % kD] = fetch(J + kD);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        });
-        const uint32_t reg = reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]);
-        if (lane == 0) partial[tile] = reg;
-    };
     if (R == static_cast<int>(T.tile_rows)) {
         const uint8_t* bp = chunks + s_base + lane16;  // buffer side
         const uint8_t* tp = bp;                        // tensor side
-        if (T.tile_rows == kWholeRows) {
+        if (MODE != kPack && T.tile_rows == kWholeRows) {
             bool whole = true;
-            if (MODE == kPack) whole = span_in_segment(cin, s_base, kWholeRows, &tp);
             if (MODE == kRestore) whole = span_in_segment(cout, s_base, kWholeRows, &tp);
             if (whole) {
                 whole_tile(std::integral_constant<int, kWholeRows>{},

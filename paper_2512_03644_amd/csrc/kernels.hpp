@@ -13,6 +13,8 @@ struct TileTables {
     const uint64_t* seg_off = nullptr;        // [n_seg + 1] stream offsets, seg_off[n_seg] = payload
     const uint64_t* seg_ptr = nullptr;        // [n_seg] device addresses
     const uint32_t* tile_first_seg = nullptr; // [n_tiles]
+    const uint64_t* tile_base = nullptr;      // [n_tiles] tensor-side address of a tile that lies
+                                              // inside one segment, else 0 (may be absent)
     const uint32_t* tab_u = nullptr;          // [4][256] multiply-by-x^8192 byte tables, then
                                               // [64] lane constants x^(128 * (63 - lane))
     uint32_t* partial = nullptr;              // [n_tiles] register of every tile run from 0

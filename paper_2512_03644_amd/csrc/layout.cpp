@@ -98,6 +98,12 @@ int build_layout(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_bytes, 
         while (si + 1 < L.segs.size() && L.segs[si].off + L.segs[si].nbytes <= s) si++;
         L.tile_first_seg[k] = static_cast<uint32_t>(si);
     }
+    L.tile_base.assign(L.n_tiles, 0);
+    for (uint64_t k = 0; k < L.n_tiles; k++) {
+        const uint64_t s = k * tile;
+        const Seg& g = L.segs[L.tile_first_seg[k]];
+        if (g.off <= s && s + tile <= g.off + g.nbytes) L.tile_base[k] = g.ptr + (s - g.off);
+    }
     return FF_OK;
 }
 

@@ -34,6 +34,10 @@ struct Layout {
     uint32_t tiles_per_chunk = 0;
     std::vector<uint32_t> tile_first_seg;  // segment holding the first byte of each tile
                                            // (segs.size()-1 for tiles past the payload)
+    // Tensor-side address of a tile's first byte if the whole tile lies inside one segment, else
+    // 0: lets a wavefront start such a tile after one table read instead of a walk through the
+    // segment tables.
+    std::vector<uint64_t> tile_base;
 };
 
 // Unit of work of the fused optimizer step: a run of elements of one parameter group (its four

@@ -31,6 +31,10 @@ int main(){
     if(L.n_tiles != L.n_chunks * L.tiles_per_chunk || L.tile_first_seg.size()!=L.n_tiles){ printf("tiling mismatch\n"); return 1; }
     for(uint64_t t=0;t<L.n_tiles;t++){ uint64_t s=t*L.tile_bytes; uint32_t f=L.tile_first_seg[t]; if(f>=L.segs.size()){printf("first seg range\n");return 1;}
       if(s<L.payload && !(L.segs[f].off<=s && s<L.segs[f].off+L.segs[f].nbytes)){printf("first seg wrong\n");return 1;} }
+    if(L.tile_base.size()!=L.n_tiles){ printf("tile_base size\n"); return 1; }
+    for(uint64_t t=0;t<L.n_tiles;t++){ uint64_t s=t*L.tile_bytes, e=s+L.tile_bytes; uint64_t want=0;
+      for(auto& g: L.segs) if(g.off<=s && e<=g.off+g.nbytes) want=g.ptr+(s-g.off);
+      if(L.tile_base[t]!=want){ printf("tile_base wrong\n"); return 1; } }
     if(L.adam_ok && !L.params.empty()){
       std::vector<WorkTile> w; build_work_tiles(L,w);
       // every payload byte covered exactly once by the tiles' streams
