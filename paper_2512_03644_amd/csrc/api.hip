@@ -22,11 +22,9 @@ struct ff_plan {
     int device = -1;
     void* dev_block = nullptr;  // one allocation holding every device table
     TileTables tables;
-    uint32_t x_tile = 0;  // x^(8 * tile_bytes)
     // A pass that only reads (verify) runs fastest on larger tiles than one that also writes:
     // it folds verify_group consecutive tiles as one.
     uint32_t verify_group = 1;
-    uint32_t x_verify_tile = 0;  // x^(8 * tile_bytes * verify_group)
     uint32_t affine = 0;  // preset/complement term of a chunk_bytes-long CRC
     // fused optimizer step (only when every parameter group is complete)
     const WorkTile* work = nullptr;
@@ -82,7 +80,8 @@ int upload_tables(ff_plan* p)
     const uint64_t o_selt = align_up(o_ftabs + kFusedTabWords * 4, 256);
     const uint64_t o_selc = align_up(o_selt + L.n_tiles * 4, 256);
     const uint64_t o_tbase = align_up(o_selc + L.n_chunks * 4, 256);
-    const uint64_t total = align_up(o_tbase + L.n_tiles * 8, 256);
+    const uint64_t o_shift = align_up(o_tbase + L.n_tiles * 8, 256);
+    const uint64_t total = align_up(o_shift + uint64_t(L.tiles_per_chunk) * 4, 256);
 
     std::vector<unsigned char> host(total, 0);
     uint64_t* h_off = reinterpret_cast<uint64_t*>(host.data() + o_off);
@@ -94,6 +93,16 @@ int upload_tables(ff_plan* p)
     h_off[n] = L.payload;
     std::memcpy(host.data() + o_first, L.tile_first_seg.data(), L.n_tiles * 4);
     std::memcpy(host.data() + o_tbase, L.tile_base.data(), L.n_tiles * 8);
+    {
+        // x^(8 * bytes behind tile k of a chunk), from the last tile (1) backwards
+        uint32_t* h_shift = reinterpret_cast<uint32_t*>(host.data() + o_shift);
+        const uint32_t x_tile = gf2_xpow(8 * L.tile_bytes);
+        uint32_t v = kOne;
+        for (uint32_t k = L.tiles_per_chunk; k-- > 0;) {
+            h_shift[k] = v;
+            v = gf2_mul(v, x_tile);
+        }
+    }
     build_tab_u(reinterpret_cast<uint32_t*>(host.data() + o_tab));
     if (!work.empty()) std::memcpy(host.data() + o_work, work.data(), work.size() * sizeof(WorkTile));
     build_fused_tabs(reinterpret_cast<uint32_t*>(host.data() + o_ftabs));
@@ -110,6 +119,7 @@ int upload_tables(ff_plan* p)
     t.seg_ptr = reinterpret_cast<const uint64_t*>(d + o_ptr);
     t.tile_first_seg = reinterpret_cast<const uint32_t*>(d + o_first);
     t.tile_base = reinterpret_cast<const uint64_t*>(d + o_tbase);
+    t.tile_shift = reinterpret_cast<const uint32_t*>(d + o_shift);
     t.tab_u = reinterpret_cast<const uint32_t*>(d + o_tab);
     t.partial = reinterpret_cast<uint32_t*>(d + o_partial);
     p->work = reinterpret_cast<const WorkTile*>(d + o_work);
@@ -160,12 +170,10 @@ int ff_snapshot_plan(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_byt
     }
     const Layout& L = p->layout;
     p->host_only = (flags & FF_PLAN_HOST_ONLY) != 0;
-    p->x_tile = gf2_xpow(8 * L.tile_bytes);
     p->affine = crc_affine_term(L.chunk_bytes);
     while (L.tile_bytes * p->verify_group < kVerifyTileBytes &&
            p->verify_group * 2 <= L.tiles_per_chunk)
         p->verify_group *= 2;  // tiles_per_chunk is a power of two
-    p->x_verify_tile = gf2_xpow(8 * L.tile_bytes * p->verify_group);
     TileTables& t = p->tables;
     t.payload = L.payload;
     t.total_rows = L.buffer_bytes / 1024;
@@ -261,8 +269,8 @@ int ff_pack(const ff_plan* p, void* chunks, uint32_t* crcs, void* hip_stream)
         return FF_ERR_INVALID;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     FF_HIP_TRY(launch_tiles(kPack, p->tables, chunks, nullptr, s));
-    FF_HIP_TRY(launch_combine_pack(p->tables.partial, p->layout.tiles_per_chunk, p->x_tile,
-                                   p->affine, p->layout.n_chunks, crcs, s));
+    FF_HIP_TRY(launch_combine_pack(p->tables.partial, p->layout.tiles_per_chunk, p->affine,
+                                   p->layout.n_chunks, crcs, s));
     return FF_OK;
 }
 
@@ -293,17 +301,17 @@ int restore_impl(const ff_plan* p, const void* chunks, const uint32_t* crcs, uin
     if (verify_only || skip_bad) {
         // pass 1: read and fold only; over the whole buffer it runs on grouped tiles
         TileTables v = t;
-        uint32_t tpc = L.tiles_per_chunk, x_tile = p->x_tile;
+        uint32_t tpc = L.tiles_per_chunk;
         if (!selected) {
             v.tile_rows *= p->verify_group;
             v.n_tiles /= p->verify_group;
             tpc /= p->verify_group;
             v.tiles_per_chunk = tpc;
-            x_tile = p->x_verify_tile;
+            v.shift_stride = p->verify_group;
         }
         FF_HIP_TRY(launch_tiles(kVerify, v, buf, n_bad, s));
-        FF_HIP_TRY(launch_combine_verify(v.partial, tpc, x_tile, p->affine, n_verify, chunk_list,
-                                         crcs, bad, n_bad, s));
+        FF_HIP_TRY(launch_combine_verify(v.partial, tpc, p->affine, n_verify, chunk_list, crcs, bad,
+                                         n_bad, s));
         if (verify_only) return FF_OK;
         // pass 2: scatter the tiles of the chunks that verified
         t.skip_bad = bad;
@@ -311,8 +319,8 @@ int restore_impl(const ff_plan* p, const void* chunks, const uint32_t* crcs, uin
         return FF_OK;
     }
     FF_HIP_TRY(launch_tiles(kRestore, t, buf, n_bad, s));
-    FF_HIP_TRY(launch_combine_verify(t.partial, L.tiles_per_chunk, p->x_tile, p->affine, n_verify,
-                                     chunk_list, crcs, bad, n_bad, s));
+    FF_HIP_TRY(launch_combine_verify(t.partial, L.tiles_per_chunk, p->affine, n_verify, chunk_list,
+                                     crcs, bad, n_bad, s));
     return FF_OK;
 }
 
@@ -436,7 +444,7 @@ int ff_pack_to_host(const ff_plan* p, void* chunks, uint32_t* crcs, void* host_c
         t.n_list = static_cast<uint32_t>(nj * L.tiles_per_chunk);
         FF_HIP_TRY(launch_tiles(kPack, t, chunks, nullptr, ps));
         FF_HIP_TRY(launch_combine_pack(t.partial + j0 * L.tiles_per_chunk, L.tiles_per_chunk,
-                                       p->x_tile, p->affine, nj, crcs + j0, ps));
+                                       p->affine, nj, crcs + j0, ps));
         FF_HIP_TRY(hipEventRecord(p->events[k], ps));
         FF_HIP_TRY(hipStreamWaitEvent(cs, p->events[k], 0));
         FF_HIP_TRY(hipMemcpyAsync(h + j0 * L.chunk_bytes, d + j0 * L.chunk_bytes,

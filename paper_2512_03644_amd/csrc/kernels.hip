@@ -194,6 +194,14 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
     const uint32_t tile = T.tile_list ? __builtin_amdgcn_readfirstlane(T.tile_list[slot])
                                       : T.tile_begin + slot;
     if (T.skip_bad && __builtin_amdgcn_readfirstlane(T.skip_bad[tile / T.tiles_per_chunk])) return;
+    // constant that moves this tile's register to the end of its chunk (tiles per chunk is a
+    // power of two); fetched now, used after the last row
+    const uint32_t shift =
+        T.tile_shift ? T.tile_shift[((tile & (T.tiles_per_chunk - 1)) + 1) * T.shift_stride - 1] : 0u;
+    auto store_register = [&](uint32_t reg) {
+        if (T.tile_shift) reg = gf2_mul(reg, shift);
+        if (lane == 0) partial[tile] = reg;
+    };
 
     // rows of this tile, as indices into the buffer's rows
     const int64_t g0 = static_cast<int64_t>(tile) * T.tile_rows - T.lead_rows;
@@ -232,8 +240,7 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
                 __builtin_amdgcn_sched_barrier(0);
             }
         });
-        const uint32_t reg = reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]);
-        if (lane == 0) partial[tile] = reg;
+        store_register(reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]));
     };
     // Pack: a default-size tile that the plan found inside one segment starts after a single
     // table read; the segment tables are walked only for the other tiles.  (Restore, whose loads
@@ -412,8 +419,7 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 });
-                const uint32_t reg = reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]);
-                if (lane == 0) partial[tile] = reg;
+                store_register(reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]));
                 return;
             }
         }
@@ -507,8 +513,7 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
         g++;
     }
 
-    const uint32_t reg = reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]);
-    if (lane == 0) partial[tile] = reg;
+    store_register(reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]));
 }
 
 // ---- combine kernels ---------------------------------------------------------------------------
@@ -521,46 +526,36 @@ __device__ __forceinline__ uint32_t chunk_register(const uint32_t* __restrict__ 
     return gf2_mul_const<kX32>(acc);  // the tiles' registers are stored without their factor x^32
 }
 
-// The same by one wavefront (result in lane 0; n a power of two): lane l folds its own run of
-// m = max(n / 64, 1) consecutive registers, then neighbouring runs are merged pairwise, the left
-// one multiplied by x_tile^(registers in the right one).
+// CRC register of a chunk from its tiles' registers, which the tile kernel stored already moved to
+// the chunk end: their XOR, times the factor x^32 that the tiles leave out.  One wavefront, n a
+// power of two, result in every lane.
 __device__ __forceinline__ uint32_t chunk_register_wave(const uint32_t* __restrict__ partial,
-                                                        uint64_t first, uint32_t n,
-                                                        uint32_t x_tile, uint32_t lane)
+                                                        uint64_t first, uint32_t n, uint32_t lane)
 {
-    const uint32_t lanes = n < kWaveSize ? n : kWaveSize;
-    const uint32_t m = n / lanes;
     uint32_t acc = 0;
-    if (lane < lanes)
-        for (uint32_t j = 0; j < m; j++)
-            acc = gf2_mul(acc, x_tile) ^ partial[first + uint64_t(lane) * m + j];
-    uint32_t xp = x_tile;  // x_tile^m, then squared level by level
-    for (uint32_t k = 1; k < m; k <<= 1) xp = gf2_mul(xp, xp);
-    for (uint32_t d = 1; d < lanes; d <<= 1) {
-        const uint32_t right = __shfl_down(acc, d);
-        if ((lane & (2 * d - 1)) == 0) acc = gf2_mul(acc, xp) ^ right;
-        xp = gf2_mul(xp, xp);
-    }
+    for (uint32_t i = lane; i < n; i += kWaveSize) acc ^= partial[first + i];
+#pragma unroll
+    for (int l = 0; l < 6; l++) acc ^= __shfl_xor(acc, 1 << l, kWaveSize);
     return gf2_mul_const<kX32>(acc);
 }
 
 constexpr int kCombineWaves = 4;  // chunks per workgroup of the combine kernels
 
 __global__ __launch_bounds__(kWaveSize* kCombineWaves) void combine_pack_kernel(
-    const uint32_t* __restrict__ partial, uint32_t tiles_per_chunk, uint32_t x_tile,
-    uint32_t affine, uint64_t n_chunks, uint32_t* __restrict__ crcs)
+    const uint32_t* __restrict__ partial, uint32_t tiles_per_chunk, uint32_t affine,
+    uint64_t n_chunks, uint32_t* __restrict__ crcs)
 {
     const uint32_t lane = threadIdx.x & (kWaveSize - 1);
     const uint64_t j = static_cast<uint64_t>(blockIdx.x) * kCombineWaves + threadIdx.x / kWaveSize;
     if (j >= n_chunks) return;
     const uint32_t reg =
-        chunk_register_wave(partial, j * tiles_per_chunk, tiles_per_chunk, x_tile, lane);
+        chunk_register_wave(partial, j * tiles_per_chunk, tiles_per_chunk, lane);
     if (lane == 0) crcs[j] = reg ^ affine;
 }
 
 __global__ __launch_bounds__(kWaveSize* kCombineWaves) void combine_verify_kernel(
-    const uint32_t* __restrict__ partial, uint32_t tiles_per_chunk, uint32_t x_tile,
-    uint32_t affine, uint64_t n_chunks, const uint32_t* __restrict__ chunk_list,
+    const uint32_t* __restrict__ partial, uint32_t tiles_per_chunk, uint32_t affine,
+    uint64_t n_chunks, const uint32_t* __restrict__ chunk_list,
     const uint32_t* __restrict__ crcs, uint32_t* __restrict__ bad, uint64_t* __restrict__ n_bad)
 {
     const uint32_t lane = threadIdx.x & (kWaveSize - 1);
@@ -568,7 +563,7 @@ __global__ __launch_bounds__(kWaveSize* kCombineWaves) void combine_verify_kerne
     if (i >= n_chunks) return;
     const uint64_t j = chunk_list ? chunk_list[i] : i;
     const uint32_t reg =
-        chunk_register_wave(partial, j * tiles_per_chunk, tiles_per_chunk, x_tile, lane);
+        chunk_register_wave(partial, j * tiles_per_chunk, tiles_per_chunk, lane);
     if (lane == 0) {
         const bool is_bad = (reg ^ affine) != crcs[j];
         bad[j] = is_bad ? 1u : 0u;
@@ -667,19 +662,18 @@ hipError_t launch_tiles(TileMode mode, const TileTables& t, void* chunks, uint64
     return hipGetLastError();
 }
 
-hipError_t launch_combine_pack(const uint32_t* partial, uint32_t tiles_per_chunk, uint32_t x_tile,
-                               uint32_t affine, uint64_t n_chunks, uint32_t* crcs,
-                               hipStream_t stream)
+hipError_t launch_combine_pack(const uint32_t* partial, uint32_t tiles_per_chunk, uint32_t affine,
+                               uint64_t n_chunks, uint32_t* crcs, hipStream_t stream)
 {
     const unsigned block = kWaveSize * kCombineWaves;  // one wavefront per chunk
     const unsigned grid = static_cast<unsigned>((n_chunks + kCombineWaves - 1) / kCombineWaves);
     hipLaunchKernelGGL(combine_pack_kernel, dim3(grid), dim3(block), 0, stream, partial,
-                       tiles_per_chunk, x_tile, affine, n_chunks, crcs);
+                       tiles_per_chunk, affine, n_chunks, crcs);
     return hipGetLastError();
 }
 
 hipError_t launch_combine_verify(const uint32_t* partial, uint32_t tiles_per_chunk,
-                                 uint32_t x_tile, uint32_t affine, uint64_t n_chunks,
+                                 uint32_t affine, uint64_t n_chunks,
                                  const uint32_t* chunk_list, const uint32_t* crcs, uint32_t* bad,
                                  uint64_t* n_bad, hipStream_t stream)
 {
@@ -687,7 +681,7 @@ hipError_t launch_combine_verify(const uint32_t* partial, uint32_t tiles_per_chu
     const unsigned block = kWaveSize * kCombineWaves;  // one wavefront per chunk
     const unsigned grid = static_cast<unsigned>((n_chunks + kCombineWaves - 1) / kCombineWaves);
     hipLaunchKernelGGL(combine_verify_kernel, dim3(grid), dim3(block), 0, stream, partial,
-                       tiles_per_chunk, x_tile, affine, n_chunks, chunk_list, crcs, bad, n_bad);
+                       tiles_per_chunk, affine, n_chunks, chunk_list, crcs, bad, n_bad);
     return hipGetLastError();
 }
 

@@ -18,6 +18,12 @@ struct TileTables {
     const uint32_t* tab_u = nullptr;          // [4][256] multiply-by-x^8192 byte tables, then
                                               // [64] lane constants x^(128 * (63 - lane))
     uint32_t* partial = nullptr;              // [n_tiles] register of every tile run from 0
+    // If set: [plan tiles per chunk] x^(8 * bytes from the end of tile k of a chunk to the end
+    // of the chunk).  A tile's register is multiplied by its entry before it is stored, so that
+    // the registers of a chunk combine by XOR alone.  A pass that folds groups of shift_stride
+    // plan tiles as one uses the entry of the group's last tile.
+    const uint32_t* tile_shift = nullptr;
+    uint32_t shift_stride = 1;
     uint64_t payload = 0;                     // N
     uint64_t total_rows = 0;                  // 1 KiB rows in the buffer
     uint32_t n_seg = 0;
@@ -45,15 +51,15 @@ enum TileMode { kPack = 0, kRestore = 1, kVerify = 2 };
 hipError_t launch_tiles(TileMode mode, const TileTables& t, void* chunks, uint64_t* n_bad,
                         hipStream_t stream);
 
-// crcs[j] = standard CRC32C of chunk j from its tiles' registers.
-hipError_t launch_combine_pack(const uint32_t* partial, uint32_t tiles_per_chunk, uint32_t x_tile,
-                               uint32_t affine, uint64_t n_chunks, uint32_t* crcs,
-                               hipStream_t stream);
+// crcs[j] = standard CRC32C of chunk j from its tiles' registers (stored moved to the chunk end,
+// see TileTables::tile_shift).
+hipError_t launch_combine_pack(const uint32_t* partial, uint32_t tiles_per_chunk, uint32_t affine,
+                               uint64_t n_chunks, uint32_t* crcs, hipStream_t stream);
 
 // bad[j] = (recomputed CRC != crcs[j]); *n_bad += number of bad chunks.  With chunk_list set,
 // only the n_chunks chunks it names are looked at.
 hipError_t launch_combine_verify(const uint32_t* partial, uint32_t tiles_per_chunk,
-                                 uint32_t x_tile, uint32_t affine, uint64_t n_chunks,
+                                 uint32_t affine, uint64_t n_chunks,
                                  const uint32_t* chunk_list, const uint32_t* crcs, uint32_t* bad,
                                  uint64_t* n_bad, hipStream_t stream);
 
