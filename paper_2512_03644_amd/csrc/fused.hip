@@ -179,7 +179,6 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
     const uint8_t* const lp = CHAINED ? C.prev + t.soff[1] : tp;
     const uint8_t* const lm = CHAINED ? C.prev + t.soff[2] : tm;
     const uint8_t* const lv = CHAINED ? C.prev + t.soff[3] : tv;
-    const int head_lane = G.pad_el / 4, head_sub = G.pad_el % 4;  // where element 0 sits in row 0
     uint32_t nonfinite = 0;  // this lane's count of infinite or NaN gradient elements (fp16 only)
 
     // A row can use vector accesses if every lane holds 4 real elements.
@@ -192,29 +191,9 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
         in.v = load16_unaligned<true>(lv + 4 * j0);
     };
 
-    // copy of a row's results for the folding wavefronts
-    auto publish = [&](Batch& out, int r, uint32_t (&fw)[2], uint32_t (&fp)[4], uint32_t (&fm)[4],
+    // copy of a row's results for the folding wavefronts, which fold them and store the full rows
+    auto publish = [&](Batch& out, uint32_t (&fw)[2], uint32_t (&fp)[4], uint32_t (&fm)[4],
                        uint32_t (&fv)[4]) {
-        // split first element: its first two bytes close the previous chunk and must not enter
-        // this tile's CRC of that stream
-        if (r == 0 && t.head_split && lane == head_lane) {
-            uint32_t* const fx[3] = {fp, fm, fv};
-#pragma unroll
-            for (int x = 1; x <= 3; x++) {
-                if (t.head_split & (1u << x)) {
-#pragma unroll
-                    for (int s = 0; s < 4; s++) {
-                        if (s == head_sub) {
-                            const uint32_t d = fx[x - 1][s];
-                            // two message bytes in the low half are M(x) * x^16; their register
-                            // is M(x) * x^32
-                            add_head_piece(crcs, t, 3 + x, d & 0xFFFFu);
-                            fx[x - 1][s] = d & 0xFFFF0000u;
-                        }
-                    }
-                }
-            }
-        }
         *reinterpret_cast<u32x2*>(&out.w[u][2 * lane]) = u32x2{fw[0], fw[1]};
         *reinterpret_cast<u32x4*>(&out.p[u][4 * lane]) = u32x4{fp[0], fp[1], fp[2], fp[3]};
         *reinterpret_cast<u32x4*>(&out.m[u][4 * lane]) = u32x4{fm[0], fm[1], fm[2], fm[3]};
@@ -222,8 +201,7 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
     };
 
     // a full row from registers
-    auto full_row_step = [&](Batch& out, int r, const RowIn& cur) {
-        const int j0 = r * kRowElems + 4 * lane - G.pad_el;  // first element of the lane
+    auto full_row_step = [&](Batch& out, const RowIn& cur) {
         uint32_t gb[4], wb[4];
         float p[4], m[4], v[4];
         gb[0] = cur.g.x & 0xFFFFu; gb[1] = cur.g.x >> 16;
@@ -247,21 +225,7 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
             fm[s] = f32_to_bits(m[s]);
             fv[s] = f32_to_bits(v[s]);
         }
-        const u32x2 w2 = {fw[0], fw[1]};
-        const u32x4 po = {fp[0], fp[1], fp[2], fp[3]};
-        const u32x4 mo = {fm[0], fm[1], fm[2], fm[3]};
-        const u32x4 vo = {fv[0], fv[1], fv[2], fv[3]};
-        store8_unaligned<true>(tw + 2 * j0, w2);
-        if constexpr (!CHAINED) {
-            store16_unaligned<true>(tp + 4 * j0, po);
-            store16_unaligned<true>(tm + 4 * j0, mo);
-            store16_unaligned<true>(tv + 4 * j0, vo);
-        }
-        store8_unaligned<true>(sw + 2 * j0, w2);
-        store16_unaligned<true>(sp + 4 * j0, po);
-        store16_unaligned<true>(sm + 4 * j0, mo);
-        store16_unaligned<true>(sv + 4 * j0, vo);
-        publish(out, r, fw, fp, fm, fv);
+        publish(out, fw, fp, fm, fv);
     };
 
     // the partial first row of a tile: element by element; absent elements stay zero
@@ -319,7 +283,7 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
             fm[s] = f32_to_bits(m[s]);
             fv[s] = f32_to_bits(v[s]);
         }
-        publish(out, r, fw, fp, fm, fv);
+        publish(out, fw, fp, fm, fv);
     };
 
     const int first = u - G.pad_rows;  // this wavefront's row of batch 0
@@ -329,7 +293,7 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
         // a virtual row (zeros) or the partial first row of the tile
         if (first < 0) {
             uint32_t zw[2] = {0, 0}, z4[4] = {0, 0, 0, 0};
-            publish(buf[0], first, zw, z4, z4, z4);
+            publish(buf[0], zw, z4, z4, z4);
         } else {
             partial_row_step(buf[0], first);
         }
@@ -346,7 +310,7 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
         const int r = first + kBatchRows * bb;
         const RowIn cur = q;
         if constexpr (decltype(prefetch_c)::value) load_row(r + 2 * kBatchRows, q);
-        full_row_step(buf[bb & 1], r, cur);
+        full_row_step(buf[bb & 1], cur);
         __syncthreads();
     };
     // steady part: the batches two ahead exist.  Its first round stands in front of the loop, so
@@ -386,15 +350,36 @@ __device__ __forceinline__ void update_role(const WorkTile& t, const TileGeom& G
     }
 }
 
-// Folding wavefront of stream x (0 = w16, 1..3 = master, m, v).
+// Folding wavefront of stream x (0 = w16, 1..3 = master, m, v): takes the rows of the previous
+// batch out of LDS, stores every full row to the snapshot and (if `tensor` is set) in place, and
+// folds it.  A wavefront thus sweeps two store streams that carry the same bytes, instead of every
+// updating wavefront scattering its row over eight; the partial first row of a tile is stored
+// element by element by the updating wavefront that produced it.
 template <class F, int DW>
-__device__ __forceinline__ uint32_t fold_stream(const TileGeom& G, Batch (&buf)[2], int x, int lane,
-                                                const uint32_t* tab, const uint32_t* lane_tab)
+__device__ __forceinline__ uint32_t fold_stream(const WorkTile& t, const TileGeom& G,
+                                                Batch (&buf)[2], int x, int lane,
+                                                uint8_t* __restrict__ tensor,
+                                                uint8_t* __restrict__ snap,
+                                                uint32_t* __restrict__ crcs, const uint32_t* tab,
+                                                const uint32_t* lane_tab)
 {
     constexpr int NE = F::NE;
     static_assert(NE % kBatchRows == 0 && F::NF == DW, "a batch never straddles the rotation");
     uint32_t S[NE][DW];
     static_for<NE>([&](auto e) { static_for<DW>([&](auto f) { S[e][f] = 0; }); });
+    const int head_lane = G.pad_el / 4, head_sub = G.pad_el % 4;  // where element 0 sits in row 0
+    auto store_row = [&](int r, const uint32_t (&d)[DW]) {
+        const int j0 = r * kRowElems + 4 * lane - G.pad_el;  // first element of the lane
+        if constexpr (DW == 2) {
+            const u32x2 w = {d[0], d[1]};
+            if (tensor) store8_unaligned<true>(tensor + 2 * j0, w);
+            store8_unaligned<true>(snap + 2 * j0, w);
+        } else {
+            const u32x4 w = {d[0], d[1], d[2], d[3]};
+            if (tensor) store16_unaligned<true>(tensor + 4 * j0, w);
+            store16_unaligned<true>(snap + 4 * j0, w);
+        }
+    };
     // start the rotation so that it is back at zero after the last batch
     int phase = (NE - (G.n_batches * kBatchRows) % NE) % NE;
     for (int b = 0; b <= G.n_batches; b++) {
@@ -407,6 +392,28 @@ __device__ __forceinline__ uint32_t fold_stream(const TileGeom& G, Batch (&buf)[
                                                           : (x == 2 ? &in.m[k][4 * lane] : &in.v[k][4 * lane]));
                 static_for<DW>([&](auto f) { d[k][f] = row[f]; });
             });
+            const int r0 = (b - 1) * kBatchRows - G.pad_rows;  // tile row of the batch's first row
+            if (b == 1) {
+                // the first batch may hold virtual rows (r < 0) and the partial row (r == 0)
+                static_for<kBatchRows>([&](auto k) {
+                    const int r = r0 + k;
+                    if (r > 0 || (r == 0 && G.pad_el == 0)) store_row(r, d[k]);
+                    // split first element: its first two bytes close the previous chunk and
+                    // must not enter this tile's CRC of that stream
+                    if (DW == 4 && r == 0 && (t.head_split & (1u << x)) && lane == head_lane) {
+                        static_for<DW>([&](auto sc) {
+                            if (sc == head_sub) {
+                                // two message bytes in the low half are M(x) * x^16; their
+                                // register is M(x) * x^32
+                                add_head_piece(crcs, t, 3 + x, d[k][sc] & 0xFFFFu);
+                                d[k][sc] &= 0xFFFF0000u;
+                            }
+                        });
+                    }
+                });
+            } else {
+                static_for<kBatchRows>([&](auto k) { store_row(r0 + k, d[k]); });
+            }
             static_for<NE / kBatchRows>([&](auto Qc) {
                 constexpr int Q = Qc;
                 if (phase == Q * kBatchRows) {
@@ -525,11 +532,17 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
         update_role<F16, CHAINED>(t, G, grad, chunks, crcs, C, buf, wave, lane);
     } else {
         const int x = wave - kUpdateWaves;
+        uint8_t* const snap = chunks + t.soff[x];
         uint32_t reg;
-        if (x == 0)
-            reg = fold_stream<B16Fold, 2>(G, buf, x, lane, lds.tab8, lds.lane8);
-        else
-            reg = fold_stream<F32Fold, 4>(G, buf, x, lane, lds.tab16, lds.lane16);
+        if (x == 0) {
+            reg = fold_stream<B16Fold, 2>(t, G, buf, x, lane, reinterpret_cast<uint8_t*>(t.ptr[0]),
+                                          snap, crcs, lds.tab8, lds.lane8);
+        } else {
+            // chained step: master, m and v live in the snapshots only
+            uint8_t* const tensor = CHAINED ? nullptr : reinterpret_cast<uint8_t*>(t.ptr[x]);
+            reg = fold_stream<F32Fold, 4>(t, G, buf, x, lane, tensor, snap, crcs, lds.tab16,
+                                          lds.lane16);
+        }
         if (lane == 0) add_piece(crcs, t, x, reg);
     }
 }
