@@ -56,7 +56,9 @@ typedef enum {
     FF_ERR_EMPTY = -3,   /* the segments hold no bytes at all                                   */
     FF_ERR_NOMEM = -4,   /* host or device allocation failed                                    */
     FF_ERR_HIP = -5,     /* a HIP runtime call or a kernel launch failed                        */
-    FF_ERR_HOST_ONLY = -6 /* device work asked of a plan built with FF_PLAN_HOST_ONLY           */
+    FF_ERR_HOST_ONLY = -6, /* device work asked of a plan built with FF_PLAN_HOST_ONLY          */
+    FF_ERR_TOO_LARGE = -7  /* input beyond the fixed capacity of an entry point that allocates
+                              nothing                                                           */
 } ff_status;
 
 typedef enum { FF_BF16 = 1, FF_F32 = 2, FF_F16 = 3 } ff_dtype;
@@ -278,6 +280,23 @@ int ff_adam_step_chained(const ff_plan *plan, const void *const *grads, const ff
  * computed by the same tile and combine kernels as ff_pack.  Allocates and frees a small
  * scratch array, so it synchronises the stream before returning. */
 int ff_crc32c(const void *dev_buf, uint64_t nbytes, uint32_t *dev_out, void *hip_stream);
+
+/*
+ * ff_crc32c for callers that cannot allocate or must not be synchronised: code that is being
+ * captured into a HIP graph, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and result as ff_crc32c, but the scratch memory (reduction tables and one CRC
+ * register per 1 MiB of input) is a fixed array in the library's device image instead of an
+ * allocation, and the call only enqueues kernels on hip_stream and returns: *dev_out is valid
+ * once the stream has reached that point.  It never calls hipMalloc or hipFree.
+ * Limits: nbytes <= FF_CRC32C_NOALLOC_MAX_BYTES, else FF_ERR_TOO_LARGE and nothing is enqueued.
+ * The array (about 260 KiB) exists once per GPU and is shared by every call on that GPU: two
+ * calls whose kernels may overlap in time (different streams) race on it and give wrong results;
+ * calls on one stream are safe back to back.  The first call on a device looks up the array's
+ * address and copies the tables into it with a blocking hipMemcpy, so make one eager call per
+ * device before capturing it into a graph.
+ */
+#define FF_CRC32C_NOALLOC_MAX_BYTES (1ull << 36) /* 64 GiB */
+int ff_crc32c_noalloc(const void *dev_buf, uint64_t nbytes, uint32_t *dev_out, void *hip_stream);
 
 /* Bench helper: plain device copy of nbytes (both DEVICE, 16-byte aligned, nbytes a multiple of
  * 16, the ranges disjoint) in the access pattern of ff_pack but without the CRC: the measured

@@ -13,7 +13,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libffsnap.so")
 
 FF_OK, FF_ERR_NULL, FF_ERR_INVALID, FF_ERR_EMPTY = 0, -1, -2, -3
-FF_ERR_NOMEM, FF_ERR_HIP, FF_ERR_HOST_ONLY = -4, -5, -6
+FF_ERR_NOMEM, FF_ERR_HIP, FF_ERR_HOST_ONLY, FF_ERR_TOO_LARGE = -4, -5, -6, -7
+FF_CRC32C_NOALLOC_MAX_BYTES = 1 << 36
 FF_BF16, FF_F32, FF_F16 = 1, 2, 3
 FF_KIND_RAW, FF_KIND_W16, FF_KIND_MASTER, FF_KIND_M, FF_KIND_V = 0, 1, 2, 3, 4
 FF_PLAN_HOST_ONLY = 1
@@ -40,7 +41,8 @@ EXPORTS = ["ff_snapshot_plan", "ff_plan_destroy", "ff_plan_payload_bytes", "ff_p
            "ff_plan_buffer_bytes", "ff_plan_chunk_bytes", "ff_plan_num_segments",
            "ff_plan_num_params", "ff_plan_layout_id", "ff_plan_segment_range",
            "ff_plan_chunk_span", "ff_razor_select", "ff_pack", "ff_pack_to_host", "ff_restore", "ff_restore_chunks", "ff_adam_step_snapshot",
-           "ff_adam_step_snapshot_f16", "ff_adam_step_chained", "ff_crc32c", "ff_copy_ceiling", "ff_strerror"]
+           "ff_adam_step_snapshot_f16", "ff_adam_step_chained", "ff_crc32c", "ff_crc32c_noalloc",
+           "ff_copy_ceiling", "ff_strerror"]
 
 
 class ff_segment(ctypes.Structure):
@@ -116,6 +118,7 @@ def lib():
                                            ctypes.POINTER(ff_adam_hparams), ctypes.c_float, vp,
                                            vp, vp, vp, vp]
         L.ff_crc32c.restype, L.ff_crc32c.argtypes = i32, [vp, u64, vp, vp]
+        L.ff_crc32c_noalloc.restype, L.ff_crc32c_noalloc.argtypes = i32, [vp, u64, vp, vp]
         L.ff_copy_ceiling.restype, L.ff_copy_ceiling.argtypes = i32, [vp, vp, u64, vp]
         L.ff_strerror.restype, L.ff_strerror.argtypes = ctypes.c_char_p, [i32]
         _lib = L
@@ -289,6 +292,10 @@ def ff_adam_step_chained(plan, grads, hparams, prev_chunks, chunks, crcs, inv_lo
 
 def ff_crc32c(buf, nbytes, out, stream=None):
     _check(lib().ff_crc32c(buf.data_ptr(), nbytes, out.data_ptr(), _stream_ptr(stream)))
+
+
+def ff_crc32c_noalloc(buf, nbytes, out, stream=None):
+    _check(lib().ff_crc32c_noalloc(buf.data_ptr(), nbytes, out.data_ptr(), _stream_ptr(stream)))
 
 
 def ff_copy_ceiling(dst, src, nbytes, stream=None):

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -15,6 +16,16 @@
 #include "layout.hpp"
 
 using namespace ffsnap;
+
+// ---- scratch of ff_crc32c_noalloc ---------------------------------------------------------------
+// The reduction tables of the tile kernel (kTabWords entries) followed by one CRC register per
+// 1 MiB tile of the buffer.  The array lives in every GPU's memory from the moment the library is
+// loaded there until the process ends.  In host code `scratch` only names the symbol: the device
+// address is looked up once per device (scratch_for_current_device) and that pointer is what the
+// kernels, and the one-time table upload, are given.
+constexpr uint32_t kNoallocTileRows = 1024;  // 1 MiB per tile, as in ff_crc32c
+constexpr uint64_t kNoallocMaxTiles = FF_CRC32C_NOALLOC_MAX_BYTES / (1024ull * kNoallocTileRows);
+static __device__ __align__(256) uint32_t scratch[kTabWords + kNoallocMaxTiles];
 
 struct ff_plan {
     Layout layout;
@@ -60,6 +71,31 @@ int hip_fail(hipError_t e)
     } while (0)
 
 uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+uint32_t* g_scratch_ptr[kMaxDevices] = {};  // per device: address of `scratch`, tables uploaded
+
+// Device address of `scratch` on the current device; on the first call per device the reduction
+// tables are written behind it (a synchronous copy: no allocation, no stream involved).
+int scratch_for_current_device(uint32_t** out)
+{
+    int dev = -1;
+    FF_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return FF_ERR_INVALID;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        uint32_t* ptr = nullptr;
+        FF_HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)));
+        if (!ptr) return FF_ERR_HIP;
+        uint32_t tab[kTabWords];
+        build_tab_u(tab);
+        FF_HIP_TRY(hipMemcpy(ptr, tab, sizeof(tab), hipMemcpyHostToDevice));
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return FF_OK;
+}
 
 
 int upload_tables(ff_plan* p)
@@ -592,6 +628,35 @@ int ff_crc32c(const void* dev_buf, uint64_t nbytes, uint32_t* dev_out, void* hip
     return rc;
 }
 
+int ff_crc32c_noalloc(const void* dev_buf, uint64_t nbytes, uint32_t* dev_out, void* hip_stream)
+{
+    if (!dev_out || (nbytes && !dev_buf)) return FF_ERR_NULL;
+    if (reinterpret_cast<uint64_t>(dev_buf) % 16 || reinterpret_cast<uint64_t>(dev_out) % 4)
+        return FF_ERR_INVALID;
+    if (nbytes > FF_CRC32C_NOALLOC_MAX_BYTES) return FF_ERR_TOO_LARGE;
+    uint32_t* ptr = nullptr;
+    const int rc = scratch_for_current_device(&ptr);
+    if (rc != FF_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const uint64_t rows = nbytes / 1024;
+    TileTables t;
+    t.total_rows = rows;
+    t.tile_rows = kNoallocTileRows;
+    t.n_tiles = static_cast<uint32_t>((rows + kNoallocTileRows - 1) / kNoallocTileRows);
+    t.lead_rows = static_cast<uint32_t>(static_cast<uint64_t>(t.n_tiles) * kNoallocTileRows - rows);
+    t.payload = rows * 1024;
+    t.tab_u = ptr;
+    // every tile of this call stores its register before the finishing kernel reads it, so what
+    // an earlier (possibly longer) call left behind is never looked at and nothing needs clearing
+    t.partial = ptr + kTabWords;
+    FF_HIP_TRY(launch_tiles(kVerify, t, const_cast<void*>(dev_buf), nullptr, s));
+    const uint8_t* tail = static_cast<const uint8_t*>(dev_buf) + rows * 1024;
+    FF_HIP_TRY(launch_finish_crc(t.partial, t.n_tiles, gf2_xpow(8ull * 1024 * kNoallocTileRows), tail,
+                                 static_cast<uint32_t>(nbytes - rows * 1024),
+                                 crc_affine_term(nbytes), dev_out, s));
+    return FF_OK;
+}
+
 int ff_copy_ceiling(void* dst, const void* src, uint64_t nbytes, void* hip_stream)
 {
     if (!dst || !src) return FF_ERR_NULL;
@@ -611,6 +676,7 @@ const char* ff_strerror(int status)
     case FF_ERR_EMPTY: return "the segments hold no bytes";
     case FF_ERR_NOMEM: return "out of memory";
     case FF_ERR_HOST_ONLY: return "device work asked of a host-only plan";
+    case FF_ERR_TOO_LARGE: return "input larger than the fixed scratch array allows";
     case FF_ERR_HIP:
         std::snprintf(buf, sizeof(buf), "HIP error: %s", g_hip_error);
         return buf;
