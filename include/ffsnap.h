@@ -26,14 +26,16 @@
  *     enqueued on it and the call returns without synchronising; results stay on the device.
  *   - Return value: FF_OK (0) or a negative ff_status.  Nothing throws, nothing aborts.
  *     Corruption found by ff_restore is reported through bad[] / n_bad, never as an error code.
- *   - A plan's layout is immutable, but the plan carries one scratch array (a partial CRC per
- *     tile, the gradient-pointer table of the fused step): two calls on the same plan must not
- *     overlap in time.  Use one plan per concurrent stream.
+ *   - A plan is immutable after ff_snapshot_plan has returned: no call writes to it or to its
+ *     device tables.  Calls on one plan may run concurrently, from several host threads and on
+ *     several streams, as long as their output arrays (chunks, crcs, bad, n_bad, and for restore
+ *     and the optimizer steps the plan's tensors) differ.  Intermediate results live in the
+ *     output arrays themselves: while a call is in flight crcs[] / bad[] hold partial sums.
  *   - Segments must not overlap each other, the chunk buffer or the crc arrays.
- *   - ff_pack, ff_restore and the fused step allocate nothing and only launch kernels, so they
- *     can be recorded into a HIP graph; the fused step copies its gradient-pointer table to the
- *     device when a pointer differs from the previous call's, so call it once eagerly with the
- *     same gradient buffers before capturing it.
+ *   - ff_pack, ff_restore, ff_restore_chunks and the optimizer steps allocate nothing, copy nothing
+ *     and only launch kernels; host arrays they are given (gradient pointers, chunk ids) are read
+ *     during the call and travel to the device inside kernel arguments.  They can therefore be
+ *     recorded into a HIP graph, which then replays with the pointers it was captured with.
  *   - A plan belongs to the device that was current when it was built; device calls made with
  *     another device current return FF_ERR_INVALID.
  */
@@ -57,8 +59,9 @@ typedef enum {
     FF_ERR_NOMEM = -4,   /* host or device allocation failed                                    */
     FF_ERR_HIP = -5,     /* a HIP runtime call or a kernel launch failed                        */
     FF_ERR_HOST_ONLY = -6, /* device work asked of a plan built with FF_PLAN_HOST_ONLY          */
-    FF_ERR_TOO_LARGE = -7  /* input beyond the fixed capacity of an entry point that allocates
+    FF_ERR_TOO_LARGE = -7, /* input beyond the fixed capacity of an entry point that allocates
                               nothing                                                           */
+    FF_ERR_LAYOUT = -8     /* the buffer was packed for another layout (ff_restore_checked)     */
 } ff_status;
 
 typedef enum { FF_BF16 = 1, FF_F32 = 2, FF_F16 = 3 } ff_dtype;
@@ -90,8 +93,9 @@ typedef struct {
  *                [10, log2(chunk_bytes)]; default 15)
  *   bits 16..18  bit 18 set: bits 16..17 choose non-temporal accesses on the tensor side (bit 16)
  *                and on the chunk-buffer side (bit 17); default both
- *   bits 19..23  order in which workgroups take tiles: 0 = default, n in 1..30 = every XCD takes
- *                runs of 2^(n-1) consecutive workgroup tiles, 31 = plain launch order            */
+ *   bits 19..23  order in which workgroups take tiles: 0 = default, n in 1..29 = every XCD takes
+ *                runs of 2^(n-1) consecutive workgroup tiles, 31 = plain launch order (30 is
+ *                FF_ERR_INVALID: a round over the 8 XCDs would exceed the 32-bit launch index)    */
 #define FF_PLAN_TILE_LOG2(n) (((uint32_t)(n) & 0xFFu) << 8)
 #define FF_PLAN_CACHE_HINT(h) (0x40000u | (((uint32_t)(h) & 3u) << 16))
 #define FF_PLAN_XCD_ORDER(n) (((uint32_t)(n) & 31u) << 19)
@@ -109,8 +113,8 @@ typedef struct {
  * Lay out a snapshot (section 4.2: the engine walks the training configuration once and
  * computes the buffer size).  segs: HOST array of n_segs descriptors, copied.  chunk_bytes: a
  * power of two in [FF_MIN_CHUNK_BYTES, FF_MAX_CHUNK_BYTES].  The plan keeps small device
- * tables (segment pointers and offsets, a tile-to-segment index, CRC constants, one partial CRC
- * per tile) on the device that is current at the time of the call.
+ * tables (segment pointers and offsets, a tile-to-segment index, CRC constants, the work list of
+ * the optimizer steps) on the device that is current at the time of the call.
  * Errors: NULL -> FF_ERR_NULL; bad chunk size / alignment / dtype / kind / reserved / flags ->
  * FF_ERR_INVALID; N == 0 -> FF_ERR_EMPTY; allocation -> FF_ERR_NOMEM; HIP -> FF_ERR_HIP.
  * On error *out is set to NULL.
@@ -197,6 +201,18 @@ int ff_restore(const ff_plan *plan, const void *chunks, const uint32_t *crcs, ui
                uint64_t *n_bad, uint32_t flags, void *hip_stream);
 
 /*
+ * ff_restore for a buffer that arrives from another worker (section 3.1 steps 5-6: the state
+ * controller forwards a healthy worker's state to the newcomer): sender_layout_id is the sender's
+ * ff_plan_layout_id(), shipped along with the buffer.  If it differs from this plan's id the two
+ * workers disagree on chunk size or tensor sizes and the buffer's bytes would land in the wrong
+ * tensors: FF_ERR_LAYOUT is returned, nothing is enqueued, no tensor, bad[] or n_bad is written.
+ * Otherwise exactly ff_restore.
+ */
+int ff_restore_checked(const ff_plan *plan, uint32_t sender_layout_id, const void *chunks,
+                       const uint32_t *crcs, uint32_t *bad, uint64_t *n_bad, uint32_t flags,
+                       void *hip_stream);
+
+/*
  * Selective state loading: the same as ff_restore for the n_ids chunks named in chunk_ids only
  * (HOST array, strictly ascending, each < num_chunks) -- the chunks a worker re-fetched after a
  * first restore flagged them, or the part of the state another source supplies (section 4.2:
@@ -230,7 +246,9 @@ typedef struct {
  * bc2s = sqrt(1 - b2^t) evaluated in double and rounded once to fp32.  master, m, v and the bf16
  * weights are overwritten in place and the same bytes are written at their stream offsets in
  * `chunks`; RAW segments are copied unchanged; crcs as in ff_pack.  The result equals ff_pack
- * run after an unfused update.  grads: HOST array of ff_plan_num_params() DEVICE pointers to
+ * run after an unfused update.  A new master, m or v that is NaN is stored as the canonical quiet
+ * NaN 0x7FC00000 (IEEE 754 leaves sign and payload of a produced NaN open and processors differ;
+ * the snapshot and its CRCs must not), and w' is rounded from the stored value: 0x7FC0.  grads: HOST array of ff_plan_num_params() DEVICE pointers to
  * bf16 gradients (2-byte aligned), indexed by param_id rank (ascending param_id); read only.
  * FF_ERR_INVALID if the plan has an incomplete group, mismatched element counts, or step == 0.
  */
@@ -243,7 +261,7 @@ int ff_adam_step_snapshot(const ff_plan *plan, const void *const *grads, const f
  * was multiplied by S, and inv_loss_scale = 1/S:
  *     g = float(grad) * inv_loss_scale   (one rounded fp32 multiplication)
  * then the arithmetic of ff_adam_step_snapshot, and w' = fp16_rne(p') (overflow gives infinity;
- * NaN keeps its sign and top 9 payload bits and is quiet).  n_nonfinite: DEVICE, one uint64,
+ * the canonical NaN that a NaN result is stored as becomes 0x7E00).  n_nonfinite: DEVICE, one uint64,
  * 8-byte aligned, or NULL: receives the number of gradient elements that are infinite or NaN.
  * The update is applied to every element regardless; a caller that lowers S on overflow goes
  * back to the previous snapshot (the paper keeps the two most recent ones, section 4.2).

@@ -18,7 +18,7 @@
  *   restore    : crc'[j] recomputed; bad[j] = crc'[j] != crc[j]; n_bad = sum(bad);
  *                every segment i gets buffer[off_i : off_i + L_i], good chunk or bad
  *   adam       : one AdamW step in fp32 with a fixed operation order (below), in place,
- *                followed by pack of the updated state
+ *                NaN results stored in one canonical form, followed by pack of the updated state
  *
  * The paper fixes none of chunking, checksum or optimizer arithmetic; the definitions above
  * are the readings taken.  CRC32C is the Castagnoli CRC of iSCSI (RFC 3720 section 12.1):
@@ -253,6 +253,20 @@ uint16_t orc_f32_to_bf16(float f)
     return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
 }
 
+/* IEEE 754 does not fix the sign or payload of a NaN that an operation produces, and processors
+ * differ (an x86 subtract hands on its NaN operand, a GPU's add of the negated operand flips the
+ * sign).  The snapshot is defined byte for byte and carries CRCs across machines, so the reading
+ * taken is: a new master, m or v that is NaN is stored as the one canonical quiet NaN 0x7FC00000,
+ * and the 16-bit weight is rounded from that stored value (bf16 0x7FC0, fp16 0x7E00). */
+static float canonical_nan(float x)
+{
+    if (isnan(x)) {
+        uint32_t u = 0x7FC00000u;
+        memcpy(&x, &u, 4);
+    }
+    return x;
+}
+
 /* Scalars every element shares: derived in double from the fp32 hyper-parameters, then
  * rounded once to fp32. */
 typedef struct {
@@ -297,9 +311,10 @@ void orc_adam_f32(uint64_t n, const uint16_t *grad, float *master, float *m, flo
         volatile float q = m1 / d;
         volatile float u = k.step_size * q;
         volatile float p1 = p - u;
+        p1 = canonical_nan(p1);
         master[i] = p1;
-        m[i] = m1;
-        v[i] = v1;
+        m[i] = canonical_nan(m1);
+        v[i] = canonical_nan(v1);
         w16[i] = orc_f32_to_bf16(p1);
     }
 }
@@ -394,9 +409,10 @@ void orc_adam_f32_f16(uint64_t n, const uint16_t *grad, float inv_scale, float *
         volatile float q = m1 / d;
         volatile float u = k.step_size * q;
         volatile float p1 = p - u;
+        p1 = canonical_nan(p1);
         master[i] = p1;
-        m[i] = m1;
-        v[i] = v1;
+        m[i] = canonical_nan(m1);
+        v[i] = canonical_nan(v1);
         w16[i] = orc_f32_to_f16(p1);
     }
     if (n_nonfinite) *n_nonfinite = bad;

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libffsnap.so")
 
 FF_OK, FF_ERR_NULL, FF_ERR_INVALID, FF_ERR_EMPTY = 0, -1, -2, -3
-FF_ERR_NOMEM, FF_ERR_HIP, FF_ERR_HOST_ONLY, FF_ERR_TOO_LARGE = -4, -5, -6, -7
+FF_ERR_NOMEM, FF_ERR_HIP, FF_ERR_HOST_ONLY, FF_ERR_TOO_LARGE, FF_ERR_LAYOUT = -4, -5, -6, -7, -8
 FF_CRC32C_NOALLOC_MAX_BYTES = 1 << 36
 FF_BF16, FF_F32, FF_F16 = 1, 2, 3
 FF_KIND_RAW, FF_KIND_W16, FF_KIND_MASTER, FF_KIND_M, FF_KIND_V = 0, 1, 2, 3, 4
@@ -31,7 +31,8 @@ def FF_PLAN_CACHE_HINT(h):
 
 
 def FF_PLAN_XCD_ORDER(n):
-    """Plan flag: every XCD takes runs of 2^(n-1) workgroup tiles (0 = default, 31 = launch order)."""
+    """Plan flag: every XCD takes runs of 2^(n-1) workgroup tiles (0 = default, 1..29, 31 = launch
+    order)."""
     return (n & 31) << 19
 
 FF_RESTORE_VERIFY_ONLY = 1
@@ -40,7 +41,7 @@ FF_RESTORE_SKIP_BAD = 2
 EXPORTS = ["ff_snapshot_plan", "ff_plan_destroy", "ff_plan_payload_bytes", "ff_plan_num_chunks",
            "ff_plan_buffer_bytes", "ff_plan_chunk_bytes", "ff_plan_num_segments",
            "ff_plan_num_params", "ff_plan_layout_id", "ff_plan_segment_range",
-           "ff_plan_chunk_span", "ff_razor_select", "ff_pack", "ff_pack_to_host", "ff_restore", "ff_restore_chunks", "ff_adam_step_snapshot",
+           "ff_plan_chunk_span", "ff_razor_select", "ff_pack", "ff_pack_to_host", "ff_restore", "ff_restore_checked", "ff_restore_chunks", "ff_adam_step_snapshot",
            "ff_adam_step_snapshot_f16", "ff_adam_step_chained", "ff_crc32c", "ff_crc32c_noalloc",
            "ff_copy_ceiling", "ff_strerror"]
 
@@ -106,6 +107,8 @@ def lib():
         L.ff_pack_to_host.restype = i32
         L.ff_pack_to_host.argtypes = [vp, vp, vp, vp, vp, u64, vp, vp]
         L.ff_restore.restype, L.ff_restore.argtypes = i32, [vp, vp, vp, vp, vp, u32, vp]
+        L.ff_restore_checked.restype = i32
+        L.ff_restore_checked.argtypes = [vp, u32, vp, vp, vp, vp, u32, vp]
         L.ff_adam_step_snapshot.restype = i32
         L.ff_adam_step_snapshot.argtypes = [vp, ctypes.POINTER(vp),
                                             ctypes.POINTER(ff_adam_hparams), vp, vp, vp]
@@ -245,6 +248,12 @@ def ff_pack_to_host(plan, chunks, crcs, host_chunks, host_crcs, slice_chunks, pa
 def ff_restore(plan, chunks, crcs, bad, n_bad, flags=0, stream=None):
     _check(lib().ff_restore(plan.handle, chunks.data_ptr(), crcs.data_ptr(), bad.data_ptr(),
                             n_bad.data_ptr(), flags, _stream_ptr(stream)))
+
+
+def ff_restore_checked(plan, sender_layout_id, chunks, crcs, bad, n_bad, flags=0, stream=None):
+    _check(lib().ff_restore_checked(plan.handle, sender_layout_id, chunks.data_ptr(),
+                                    crcs.data_ptr(), bad.data_ptr(), n_bad.data_ptr(), flags,
+                                    _stream_ptr(stream)))
 
 
 def ff_restore_chunks(plan, chunks, crcs, chunk_ids, bad, n_bad, flags=0, stream=None):

@@ -27,6 +27,9 @@ constexpr uint32_t kNoallocTileRows = 1024;  // 1 MiB per tile, as in ff_crc32c
 constexpr uint64_t kNoallocMaxTiles = FF_CRC32C_NOALLOC_MAX_BYTES / (1024ull * kNoallocTileRows);
 static __device__ __align__(256) uint32_t scratch[kTabWords + kNoallocMaxTiles];
 
+// Nothing in a plan changes after ff_snapshot_plan has returned: every call reads it, and the
+// device tables behind it, only.  What a call needs beyond them travels in kernel arguments or
+// lives in the caller's own output arrays.
 struct ff_plan {
     Layout layout;
     bool host_only = false;
@@ -42,16 +45,9 @@ struct ff_plan {
     uint32_t n_work = 0;        // all work tiles: parameter tiles first, then RAW tiles
     uint32_t n_work_param = 0;
     uint32_t fused_xcd_group = 4;  // XCD-aware order of the fused step's tiles (kernels.hpp)
-    uint64_t* grads = nullptr;        // [n_params] device copy of the caller's gradient pointers
+    // entry k: first parameter tile of parameter group k * kGradsPerLaunch; last entry: n_work_param
+    std::vector<uint32_t> group_tile_begin;
     const uint32_t* fused_tabs = nullptr;
-    // selective restore: device lists of the chosen tiles / chunks
-    uint32_t* sel_tiles = nullptr;    // [n_tiles]
-    uint32_t* sel_chunks = nullptr;   // [n_chunks]
-    // Host staging of per-call tables: asynchronous copies read from here, so the caller's arrays
-    // are never touched after the call returns.  (One call at a time per plan.)
-    mutable std::vector<hipEvent_t> events;  // one per slice of ff_pack_to_host, created on demand
-    mutable std::vector<uint64_t> host_grads;
-    mutable std::vector<uint32_t> host_sel;
 };
 
 namespace {
@@ -106,16 +102,12 @@ int upload_tables(ff_plan* p)
     const uint64_t o_ptr = align_up(o_off + (n + 1) * 8, 256);
     const uint64_t o_first = align_up(o_ptr + n * 8, 256);
     const uint64_t o_tab = align_up(o_first + L.n_tiles * 4, 256);
-    const uint64_t o_partial = align_up(o_tab + kTabWords * 4, 256);
     std::vector<WorkTile> work;
     if (L.adam_ok && !L.params.empty()) build_work_tiles(L, work);
     if (work.size() > 0xFFFFFFF0ull) return FF_ERR_INVALID;
-    const uint64_t o_work = align_up(o_partial + L.n_tiles * 4, 256);
-    const uint64_t o_grads = align_up(o_work + work.size() * sizeof(WorkTile), 256);
-    const uint64_t o_ftabs = align_up(o_grads + L.params.size() * 8, 256);
-    const uint64_t o_selt = align_up(o_ftabs + kFusedTabWords * 4, 256);
-    const uint64_t o_selc = align_up(o_selt + L.n_tiles * 4, 256);
-    const uint64_t o_tbase = align_up(o_selc + L.n_chunks * 4, 256);
+    const uint64_t o_work = align_up(o_tab + kTabWords * 4, 256);
+    const uint64_t o_ftabs = align_up(o_work + work.size() * sizeof(WorkTile), 256);
+    const uint64_t o_tbase = align_up(o_ftabs + kFusedTabWords * 4, 256);
     const uint64_t o_shift = align_up(o_tbase + L.n_tiles * 8, 256);
     const uint64_t total = align_up(o_shift + uint64_t(L.tiles_per_chunk) * 4, 256);
 
@@ -130,10 +122,11 @@ int upload_tables(ff_plan* p)
     std::memcpy(host.data() + o_first, L.tile_first_seg.data(), L.n_tiles * 4);
     std::memcpy(host.data() + o_tbase, L.tile_base.data(), L.n_tiles * 8);
     {
-        // x^(8 * bytes behind tile k of a chunk), from the last tile (1) backwards
+        // x^(32 + 8 * bytes behind tile k of a chunk), from the last tile (x^32) backwards: the
+        // factor x^32 is the one a tile's register lacks
         uint32_t* h_shift = reinterpret_cast<uint32_t*>(host.data() + o_shift);
         const uint32_t x_tile = gf2_xpow(8 * L.tile_bytes);
-        uint32_t v = kOne;
+        uint32_t v = kX32;
         for (uint32_t k = L.tiles_per_chunk; k-- > 0;) {
             h_shift[k] = v;
             v = gf2_mul(v, x_tile);
@@ -157,15 +150,18 @@ int upload_tables(ff_plan* p)
     t.tile_base = reinterpret_cast<const uint64_t*>(d + o_tbase);
     t.tile_shift = reinterpret_cast<const uint32_t*>(d + o_shift);
     t.tab_u = reinterpret_cast<const uint32_t*>(d + o_tab);
-    t.partial = reinterpret_cast<uint32_t*>(d + o_partial);
     p->work = reinterpret_cast<const WorkTile*>(d + o_work);
     p->n_work = static_cast<uint32_t>(work.size());
     p->n_work_param = 0;
     for (const WorkTile& w : work) p->n_work_param += (w.kind == kWorkParam) ? 1u : 0u;
-    p->grads = reinterpret_cast<uint64_t*>(d + o_grads);
+    // the parameter tiles are sorted by parameter group: where each launch of the fused step begins
+    p->group_tile_begin.clear();
+    for (uint32_t i = 0; i < p->n_work_param; i++)
+        while (p->group_tile_begin.size() <= work[i].grad_index / kGradsPerLaunch)
+            p->group_tile_begin.push_back(i);
+    while (p->group_tile_begin.size() <= (L.params.size() + kGradsPerLaunch - 1) / kGradsPerLaunch)
+        p->group_tile_begin.push_back(p->n_work_param);
     p->fused_tabs = reinterpret_cast<const uint32_t*>(d + o_ftabs);
-    p->sel_tiles = reinterpret_cast<uint32_t*>(d + o_selt);
-    p->sel_chunks = reinterpret_cast<uint32_t*>(d + o_selc);
     return FF_OK;
 }
 
@@ -218,11 +214,16 @@ int ff_snapshot_plan(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_byt
     t.lead_rows = 0;
     t.n_tiles = static_cast<uint32_t>(L.n_tiles);
     t.tiles_per_chunk = L.tiles_per_chunk;
+    while ((1u << t.tpc_log2) < L.tiles_per_chunk) t.tpc_log2++;
     // bits 16..18: bit 18 set = take bits 16..17 as the cache-hint selector (tuning knob)
     if (flags & 0x40000u) t.hint = (flags >> 16) & 3u;
     // bits 19..23: 0 = default, else log2(xcd_group) + 1, 31 = no regrouping (tuning knob)
     {
         const unsigned xg = (flags >> 19) & 31u;
+        if (xg == 30u) {  // 8 * 2^29 workgroups per round does not fit the 32-bit launch index
+            delete p;
+            return FF_ERR_INVALID;
+        }
         if (xg == 31u) t.xcd_group = p->fused_xcd_group = 0;
         else if (xg) t.xcd_group = p->fused_xcd_group = 1u << (xg - 1);
     }
@@ -249,7 +250,6 @@ int ff_snapshot_plan(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_byt
 void ff_plan_destroy(ff_plan* plan)
 {
     if (!plan) return;
-    for (hipEvent_t e : plan->events) (void)hipEventDestroy(e);
     if (plan->dev_block) (void)hipFree(plan->dev_block);
     delete plan;
 }
@@ -304,9 +304,10 @@ int ff_pack(const ff_plan* p, void* chunks, uint32_t* crcs, void* hip_stream)
     if (reinterpret_cast<uint64_t>(chunks) % 16 || reinterpret_cast<uint64_t>(crcs) % 4)
         return FF_ERR_INVALID;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    FF_HIP_TRY(launch_tiles(kPack, p->tables, chunks, nullptr, s));
-    FF_HIP_TRY(launch_combine_pack(p->tables.partial, p->layout.tiles_per_chunk, p->affine,
-                                   p->layout.n_chunks, crcs, s));
+    TileTables t = p->tables;
+    t.acc = crcs;
+    FF_HIP_TRY(launch_preset(crcs, nullptr, 0, p->layout.n_chunks, p->affine, nullptr, nullptr, s));
+    FF_HIP_TRY(launch_tiles(kPack, t, chunks, s));
     return FF_OK;
 }
 
@@ -314,49 +315,41 @@ int ff_pack(const ff_plan* p, void* chunks, uint32_t* crcs, void* hip_stream)
 
 namespace {
 
-// Verify (and scatter) either every chunk or the chunks listed in the plan's selection tables.
+// Verify (and scatter) either every chunk or the chunks of `list` (at most kMaxListedChunks; a
+// longer selection is a sequence of these).  clear_n_bad: this call starts the count.
 int restore_impl(const ff_plan* p, const void* chunks, const uint32_t* crcs, uint32_t* bad,
-                 uint64_t* n_bad, uint32_t flags, bool selected, uint32_t n_sel_chunks,
+                 uint64_t* n_bad, uint32_t flags, const ChunkList* list, bool clear_n_bad,
                  hipStream_t s)
 {
     const Layout& L = p->layout;
     TileTables t = p->tables;
-    if (selected) {
-        t.tile_list = p->sel_tiles;
-        t.n_list = n_sel_chunks * L.tiles_per_chunk;
-    }
-    const uint32_t* chunk_list = selected ? p->sel_chunks : nullptr;
-    const uint64_t n_verify = selected ? n_sel_chunks : L.n_chunks;
+    t.acc = bad;  // the tiles' registers are summed in the caller's bad[]
     void* buf = const_cast<void*>(chunks);
-    if (selected && n_sel_chunks == 0) {
-        FF_HIP_TRY(launch_zero_u64(n_bad, s));
-        return FF_OK;
-    }
     const bool verify_only = (flags & FF_RESTORE_VERIFY_ONLY) != 0;
     const bool skip_bad = (flags & FF_RESTORE_SKIP_BAD) != 0;
+    FF_HIP_TRY(launch_preset(bad, crcs, 0, L.n_chunks, p->affine, clear_n_bad ? n_bad : nullptr, list, s));
     if (verify_only || skip_bad) {
         // pass 1: read and fold only; over the whole buffer it runs on grouped tiles
         TileTables v = t;
-        uint32_t tpc = L.tiles_per_chunk;
-        if (!selected) {
+        if (!list) {
             v.tile_rows *= p->verify_group;
             v.n_tiles /= p->verify_group;
-            tpc /= p->verify_group;
-            v.tiles_per_chunk = tpc;
+            v.tiles_per_chunk /= p->verify_group;
+            v.tpc_log2 = 0;
+            while ((1u << v.tpc_log2) < v.tiles_per_chunk) v.tpc_log2++;
             v.shift_stride = p->verify_group;
         }
-        FF_HIP_TRY(launch_tiles(kVerify, v, buf, n_bad, s));
-        FF_HIP_TRY(launch_combine_verify(v.partial, tpc, p->affine, n_verify, chunk_list, crcs, bad,
-                                         n_bad, s));
+        FF_HIP_TRY(launch_tiles(kVerify, v, buf, s, list));
+        FF_HIP_TRY(launch_finish_verify(bad, L.n_chunks, n_bad, list, s));
         if (verify_only) return FF_OK;
-        // pass 2: scatter the tiles of the chunks that verified
+        // pass 2: scatter the tiles of the chunks that verified; nothing is folded
+        t.acc = nullptr;
         t.skip_bad = bad;
-        FF_HIP_TRY(launch_tiles(kRestore, t, buf, nullptr, s));
+        FF_HIP_TRY(launch_tiles(kRestore, t, buf, s, list));
         return FF_OK;
     }
-    FF_HIP_TRY(launch_tiles(kRestore, t, buf, n_bad, s));
-    FF_HIP_TRY(launch_combine_verify(t.partial, L.tiles_per_chunk, p->affine, n_verify, chunk_list,
-                                     crcs, bad, n_bad, s));
+    FF_HIP_TRY(launch_tiles(kRestore, t, buf, s, list));
+    FF_HIP_TRY(launch_finish_verify(bad, L.n_chunks, n_bad, list, s));
     return FF_OK;
 }
 
@@ -414,31 +407,11 @@ int adam_impl(const ff_plan* p, const void* const* grads, const ff_adam_hparams*
     c.xcd_group = p->fused_xcd_group;
     c.n_nonfinite = n_nonfinite;
     c.prev = static_cast<const uint8_t*>(prev);
-    // The device table of gradient pointers is refreshed only when a pointer differs from the last
-    // call's (a training loop passes the same buffers every step).  The array is copied into the
-    // plan first: the asynchronous upload reads from there.
-    bool same = p->host_grads.size() == L.params.size();
-    for (size_t i = 0; same && i < L.params.size(); i++)
-        same = p->host_grads[i] == reinterpret_cast<uint64_t>(grads[i]);
-    if (!same) {
-        try {
-            p->host_grads.resize(L.params.size());
-        } catch (const std::bad_alloc&) {
-            return FF_ERR_NOMEM;
-        }
-        for (size_t i = 0; i < L.params.size(); i++)
-            p->host_grads[i] = reinterpret_cast<uint64_t>(grads[i]);
-        const hipError_t e = hipMemcpyAsync(p->grads, p->host_grads.data(),
-                                            L.params.size() * sizeof(uint64_t),
-                                            hipMemcpyHostToDevice, s);
-        if (e != hipSuccess) {
-            p->host_grads.clear();  // the device table is in an unknown state
-            return hip_fail(e);
-        }
-    }
     FF_HIP_TRY(launch_fused(half_dtype == FF_F16, p->work, p->n_work_param,
-                            p->n_work - p->n_work_param, p->grads, p->fused_tabs,
-                            chunks, crcs, L.n_chunks, L.payload, L.buffer_bytes, p->affine, c, s));
+                            p->n_work - p->n_work_param, grads,
+                            static_cast<uint32_t>(L.params.size()), p->group_tile_begin.data(),
+                            p->fused_tabs, chunks, crcs, L.n_chunks, L.payload, L.buffer_bytes,
+                            p->affine, c, s));
     return FF_OK;
 }
 
@@ -461,28 +434,26 @@ int ff_pack_to_host(const ff_plan* p, void* chunks, uint32_t* crcs, void* host_c
     hipStream_t ps = static_cast<hipStream_t>(pack_stream);
     hipStream_t cs = static_cast<hipStream_t>(copy_stream);
     const uint64_t n_slices = (L.n_chunks + slice_chunks - 1) / slice_chunks;
-    try {
-        while (p->events.size() < n_slices) {
-            hipEvent_t e;
-            FF_HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-            p->events.push_back(e);
-        }
-    } catch (const std::bad_alloc&) {
-        return FF_ERR_NOMEM;
-    }
     uint8_t* d = static_cast<uint8_t*>(chunks);
     uint8_t* h = static_cast<uint8_t*>(host_chunks);
     for (uint64_t k = 0; k < n_slices; k++) {
         const uint64_t j0 = k * slice_chunks;
         const uint64_t nj = std::min(slice_chunks, L.n_chunks - j0);
         TileTables t = p->tables;
+        t.acc = crcs;
         t.tile_begin = static_cast<uint32_t>(j0 * L.tiles_per_chunk);
         t.n_list = static_cast<uint32_t>(nj * L.tiles_per_chunk);
-        FF_HIP_TRY(launch_tiles(kPack, t, chunks, nullptr, ps));
-        FF_HIP_TRY(launch_combine_pack(t.partial + j0 * L.tiles_per_chunk, L.tiles_per_chunk,
-                                       p->affine, nj, crcs + j0, ps));
-        FF_HIP_TRY(hipEventRecord(p->events[k], ps));
-        FF_HIP_TRY(hipStreamWaitEvent(cs, p->events[k], 0));
+        FF_HIP_TRY(launch_preset(crcs, nullptr, j0, nj, p->affine, nullptr, nullptr, ps));
+        FF_HIP_TRY(launch_tiles(kPack, t, chunks, ps));
+        // the copy stream waits for this slice; the event belongs to this call alone and is
+        // released as soon as the wait has been queued (the runtime keeps it until then)
+        hipEvent_t done;
+        FF_HIP_TRY(hipEventCreateWithFlags(&done, hipEventDisableTiming));
+        hipError_t e = hipEventRecord(done, ps);
+        if (e == hipSuccess) e = hipStreamWaitEvent(cs, done, 0);
+        const hipError_t e2 = hipEventDestroy(done);
+        FF_HIP_TRY(e);
+        FF_HIP_TRY(e2);
         FF_HIP_TRY(hipMemcpyAsync(h + j0 * L.chunk_bytes, d + j0 * L.chunk_bytes,
                                   nj * L.chunk_bytes, hipMemcpyDeviceToHost, cs));
         FF_HIP_TRY(hipMemcpyAsync(host_crcs + j0, crcs + j0, nj * 4, hipMemcpyDeviceToHost, cs));
@@ -495,7 +466,18 @@ int ff_restore(const ff_plan* p, const void* chunks, const uint32_t* crcs, uint3
 {
     int rc = check_restore_args(p, chunks, crcs, bad, n_bad, flags);
     if (rc != FF_OK) return rc;
-    return restore_impl(p, chunks, crcs, bad, n_bad, flags, false, 0,
+    return restore_impl(p, chunks, crcs, bad, n_bad, flags, nullptr, true,
+                        static_cast<hipStream_t>(hip_stream));
+}
+
+int ff_restore_checked(const ff_plan* p, uint32_t sender_layout_id, const void* chunks,
+                       const uint32_t* crcs, uint32_t* bad, uint64_t* n_bad, uint32_t flags,
+                       void* hip_stream)
+{
+    int rc = check_restore_args(p, chunks, crcs, bad, n_bad, flags);
+    if (rc != FF_OK) return rc;
+    if (sender_layout_id != p->layout.layout_id) return FF_ERR_LAYOUT;  // nothing enqueued
+    return restore_impl(p, chunks, crcs, bad, n_bad, flags, nullptr, true,
                         static_cast<hipStream_t>(hip_stream));
 }
 
@@ -513,24 +495,20 @@ int ff_restore_chunks(const ff_plan* p, const void* chunks, const uint32_t* crcs
         if (k && chunk_ids[k] <= chunk_ids[k - 1]) return FF_ERR_INVALID;  // strictly ascending
     }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const uint64_t tpc = L.tiles_per_chunk;
-    try {
-        p->host_sel.resize(n_ids * (tpc + 1));
-    } catch (const std::bad_alloc&) {
-        return FF_ERR_NOMEM;
+    if (n_ids == 0) {
+        FF_HIP_TRY(launch_zero_u64(n_bad, s));
+        return FF_OK;
     }
-    uint32_t* h_chunks = p->host_sel.data();
-    uint32_t* h_tiles = h_chunks + n_ids;
-    for (uint64_t k = 0; k < n_ids; k++) {
-        h_chunks[k] = static_cast<uint32_t>(chunk_ids[k]);
-        for (uint64_t i = 0; i < tpc; i++)
-            h_tiles[k * tpc + i] = static_cast<uint32_t>(chunk_ids[k] * tpc + i);
+    // the ids go to the kernels inside their arguments, kMaxListedChunks at a time
+    for (uint64_t k0 = 0; k0 < n_ids; k0 += kMaxListedChunks) {
+        ChunkList list;
+        list.n = static_cast<uint32_t>(std::min<uint64_t>(kMaxListedChunks, n_ids - k0));
+        for (uint32_t k = 0; k < kMaxListedChunks; k++)
+            list.id[k] = k < list.n ? static_cast<uint32_t>(chunk_ids[k0 + k]) : 0u;
+        rc = restore_impl(p, chunks, crcs, bad, n_bad, flags, &list, k0 == 0, s);
+        if (rc != FF_OK) return rc;
     }
-    if (n_ids) {
-        FF_HIP_TRY(hipMemcpyAsync(p->sel_chunks, h_chunks, n_ids * 4, hipMemcpyHostToDevice, s));
-        FF_HIP_TRY(hipMemcpyAsync(p->sel_tiles, h_tiles, n_ids * tpc * 4, hipMemcpyHostToDevice, s));
-    }
-    return restore_impl(p, chunks, crcs, bad, n_bad, flags, true, static_cast<uint32_t>(n_ids), s);
+    return FF_OK;
 }
 
 int ff_plan_chunk_span(const ff_plan* p, uint64_t chunk, uint64_t* first_seg, uint64_t* n_seg,
@@ -615,7 +593,7 @@ int ff_crc32c(const void* dev_buf, uint64_t nbytes, uint32_t* dev_out, void* hip
         if ((e = hipMemcpyAsync(scratch, tab, sizeof(tab), hipMemcpyHostToDevice, s)) != hipSuccess) break;
         t.tab_u = static_cast<const uint32_t*>(scratch);
         t.partial = static_cast<uint32_t*>(scratch) + kTabWords;
-        if ((e = launch_tiles(kVerify, t, const_cast<void*>(dev_buf), nullptr, s)) != hipSuccess) break;
+        if ((e = launch_tiles(kVerify, t, const_cast<void*>(dev_buf), s)) != hipSuccess) break;
         const uint8_t* tail = static_cast<const uint8_t*>(dev_buf) + rows * 1024;
         e = launch_finish_crc(t.partial, t.n_tiles, gf2_xpow(8ull * 1024 * tile_rows), tail,
                               static_cast<uint32_t>(nbytes - rows * 1024), crc_affine_term(nbytes),
@@ -649,7 +627,7 @@ int ff_crc32c_noalloc(const void* dev_buf, uint64_t nbytes, uint32_t* dev_out, v
     // every tile of this call stores its register before the finishing kernel reads it, so what
     // an earlier (possibly longer) call left behind is never looked at and nothing needs clearing
     t.partial = ptr + kTabWords;
-    FF_HIP_TRY(launch_tiles(kVerify, t, const_cast<void*>(dev_buf), nullptr, s));
+    FF_HIP_TRY(launch_tiles(kVerify, t, const_cast<void*>(dev_buf), s));
     const uint8_t* tail = static_cast<const uint8_t*>(dev_buf) + rows * 1024;
     FF_HIP_TRY(launch_finish_crc(t.partial, t.n_tiles, gf2_xpow(8ull * 1024 * kNoallocTileRows), tail,
                                  static_cast<uint32_t>(nbytes - rows * 1024),
@@ -677,6 +655,7 @@ const char* ff_strerror(int status)
     case FF_ERR_NOMEM: return "out of memory";
     case FF_ERR_HOST_ONLY: return "device work asked of a host-only plan";
     case FF_ERR_TOO_LARGE: return "input larger than the fixed scratch array allows";
+    case FF_ERR_LAYOUT: return "the sender's layout id differs from the plan's";
     case FF_ERR_HIP:
         std::snprintf(buf, sizeof(buf), "HIP error: %s", g_hip_error);
         return buf;

@@ -58,8 +58,16 @@ __device__ __forceinline__ uint32_t f32_to_f16_bits(float f)
     return __half_as_ushort(__float2half_rn(f));
 }
 
+// IEEE 754 leaves sign and payload of a NaN that an operation produces open, and processors differ
+// in them.  A snapshot is compared byte for byte and CRC'd across machines, so a NaN result of the
+// update is stored in one form: quiet, positive, empty payload.
+constexpr uint32_t kCanonicalNaN = 0x7FC00000u;
+__device__ __forceinline__ float canonical_nan(float x) { return (x != x) ? bits_to_f32(kCanonicalNaN) : x; }
+
 // One element of the update; every operation is a separately rounded fp32 operation (the file
-// is compiled with -ffp-contract=off, division and square root are correctly rounded).
+// is compiled with -ffp-contract=off, division and square root are correctly rounded).  New
+// master, m and v that are NaN are stored as the canonical NaN, and the 16-bit weight is rounded
+// from that.
 // F16: the gradient is fp16 of a loss scaled by S and is multiplied by inv_scale = 1/S first;
 // the working weight is rounded to fp16.  Otherwise both are bf16 and nothing is scaled.
 template <bool F16>
@@ -79,10 +87,10 @@ __device__ __forceinline__ void adam_element(const FusedConsts& C, uint32_t g_bi
     // rounded to one (wave-uniform test; beta2 = 0.95 gets there at step 333)
     const float r = sqrtf(v1);
     const float d = ((k.bc2s == 1.0f) ? r : (r / k.bc2s)) + k.eps;
-    const float p1 = pd - (k.step_size * (m1 / d));
+    const float p1 = canonical_nan(pd - (k.step_size * (m1 / d)));
     p = p1;
-    m = m1;
-    v = v1;
+    m = canonical_nan(m1);
+    v = canonical_nan(v1);
     w_bits = F16 ? f32_to_f16_bits(p1) : f32_to_bf16_bits(p1);
 }
 
@@ -496,11 +504,14 @@ __device__ __forceinline__ void run_raw_tile(const WorkTile& t, uint8_t* __restr
     if (lane == 0) add_piece(crcs, t, 0, reg);
 }
 
+// The gradient pointers of the parameter groups [grad_base, grad_base + kGradsPerLaunch) travel by
+// value in the kernel arguments: the step keeps no per-call table in device memory, so calls on
+// one plan may overlap and a captured launch carries its own pointers.
 template <bool F16, bool CHAINED>
 __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
-    const WorkTile* __restrict__ tiles, uint32_t n_tiles, const uint64_t* __restrict__ grads,
+    const WorkTile* __restrict__ tiles, uint32_t n_tiles, uint32_t grad_base,
     const uint32_t* __restrict__ tabs, uint8_t* __restrict__ chunks, uint32_t* __restrict__ crcs,
-    FusedConsts C)
+    FusedConsts C, GradPtrs grads)
 {
     __shared__ Lds lds;
     __shared__ Batch buf[2];
@@ -528,7 +539,7 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
     // every wavefront of the workgroup passes the same n_batches + 1 barriers
     const TileGeom G = tile_geom(t);
     if (wave < kUpdateWaves) {
-        const uint8_t* grad = reinterpret_cast<const uint8_t*>(grads[t.grad_index]);
+        const uint8_t* grad = reinterpret_cast<const uint8_t*>(grads.p[t.grad_index - grad_base]);
         update_role<F16, CHAINED>(t, G, grad, chunks, crcs, C, buf, wave, lane);
     } else {
         const int x = wave - kUpdateWaves;
@@ -597,10 +608,10 @@ void build_fused_tabs(uint32_t* tab)
 }
 
 hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_param_tiles,
-                        uint32_t n_raw_tiles, const uint64_t* grads,
-                        const uint32_t* tabs, void* chunks, uint32_t* crcs, uint64_t n_chunks,
-                        uint64_t payload, uint64_t buffer_bytes, uint32_t affine,
-                        const FusedConsts& consts, hipStream_t stream)
+                        uint32_t n_raw_tiles, const void* const* grads, uint32_t n_params,
+                        const uint32_t* group_tile_begin, const uint32_t* tabs, void* chunks,
+                        uint32_t* crcs, uint64_t n_chunks, uint64_t payload, uint64_t buffer_bytes,
+                        uint32_t affine, const FusedConsts& consts, hipStream_t stream)
 {
     uint8_t* c = static_cast<uint8_t*>(chunks);
     const uint64_t prep_items = n_chunks > (buffer_bytes - payload) / 2 ? n_chunks
@@ -612,12 +623,17 @@ hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_param_tiles,
                        affine, c, payload, buffer_bytes, f16 ? consts.n_nonfinite : nullptr);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (n_param_tiles) {
-        const dim3 grid(n_param_tiles), block(kWaveSize * kWavesPerBlock);
-        auto kernel = consts.prev ? (f16 ? fused_kernel<true, true> : fused_kernel<false, true>)
-                                  : (f16 ? fused_kernel<true, false> : fused_kernel<false, false>);
-        hipLaunchKernelGGL(kernel, grid, block, 0, stream, tiles, n_param_tiles, grads, tabs, c, crcs,
-                           consts);
+    auto kernel = consts.prev ? (f16 ? fused_kernel<true, true> : fused_kernel<false, true>)
+                              : (f16 ? fused_kernel<true, false> : fused_kernel<false, false>);
+    // one launch per kGradsPerLaunch parameter groups; the parameter tiles are sorted by group
+    for (uint32_t k = 0, p0 = 0; p0 < n_params && n_param_tiles; k++, p0 += kGradsPerLaunch) {
+        const uint32_t t0 = group_tile_begin[k], t1 = group_tile_begin[k + 1];
+        if (t1 == t0) continue;
+        GradPtrs g;
+        for (uint32_t i = 0; i < kGradsPerLaunch; i++)
+            g.p[i] = p0 + i < n_params ? reinterpret_cast<uint64_t>(grads[p0 + i]) : 0;
+        hipLaunchKernelGGL(kernel, dim3(t1 - t0), dim3(kWaveSize * kWavesPerBlock), 0, stream,
+                           tiles + t0, t1 - t0, p0, tabs, c, crcs, consts, g);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -29,14 +29,23 @@ struct FusedConsts {
 constexpr int kFusedTabWords = 2048 + 128;
 void build_fused_tabs(uint32_t* tab);
 
-// Enqueues prepare (crcs = affine, zero tail, counter = 0) and the tile kernel.
-// tiles/grads/tabs: device tables (tabs = tables for 1024-byte rows, then for 512-byte rows).
-// f16: gradients and working weights are fp16 (else bf16).  tiles: the parameter tiles first, then
-// the RAW tiles (a kernel of their own).
+// Gradient pointers of up to kGradsPerLaunch consecutive parameter groups, handed to the kernel by
+// value in its arguments (3 KiB).
+constexpr uint32_t kGradsPerLaunch = 384;
+struct GradPtrs {
+    uint64_t p[kGradsPerLaunch];
+};
+
+// Enqueues prepare (crcs = affine, zero tail, counter = 0) and the tile kernels.
+// tiles/tabs: device tables (tabs = tables for 1024-byte rows, then for 512-byte rows); tiles holds
+// the parameter tiles first, sorted by parameter group, then the RAW tiles (a kernel of their own).
+// grads: HOST array of n_params device pointers, read during the call only.  group_tile_begin:
+// HOST array, entry k = index of the first parameter tile of group k * kGradsPerLaunch, one more
+// entry = n_param_tiles.  f16: gradients and working weights are fp16 (else bf16).
 hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_param_tiles,
-                        uint32_t n_raw_tiles, const uint64_t* grads,
-                        const uint32_t* tabs, void* chunks, uint32_t* crcs, uint64_t n_chunks,
-                        uint64_t payload, uint64_t buffer_bytes, uint32_t affine,
-                        const FusedConsts& consts, hipStream_t stream);
+                        uint32_t n_raw_tiles, const void* const* grads, uint32_t n_params,
+                        const uint32_t* group_tile_begin, const uint32_t* tabs, void* chunks,
+                        uint32_t* crcs, uint64_t n_chunks, uint64_t payload, uint64_t buffer_bytes,
+                        uint32_t affine, const FusedConsts& consts, hipStream_t stream);
 
 }  // namespace ffsnap

@@ -15,9 +15,12 @@
 // multiples of the CRC generator (fold_taps.h).  That is 36 XORs per 16 bytes and is exact
 // GF(2) algebra.  Only at the end of a tile are the NE*4 dwords of every lane reduced to one
 // 32-bit register: Horner steps with byte tables (multiply by x^8192) held in LDS, then
-// bitwise multiplications to merge columns and lanes.  A second, tiny kernel merges the tile
-// registers of a chunk with x^(8*tile_bytes) multiplications and adds the preset/complement
-// term, which gives the standard CRC32C of the chunk.
+// bitwise multiplications to merge columns and lanes.  The tile multiplies that register by
+// x^(8 * bytes between its end and the end of its chunk) and XORs it, with an atomic, into the
+// chunk's word of the caller's own output array (crcs[] for pack, bad[] for restore/verify), which
+// a small kernel has preset with the preset/complement term of the CRC.  XOR commutes, so the
+// result does not depend on the order in which tiles finish, and no memory outside the caller's
+// arrays is written: calls on one plan may overlap in time.
 #include "kernels.hpp"
 
 #include "fold.h"
@@ -176,32 +179,28 @@ __device__ __forceinline__ void fold_word(uint32_t (&S)[kNE][kNF], u32x4 w)
 // group (virtual rows at the tile start, a segment boundary, the end of the payload) takes the
 // guarded path row by row.
 template <int MODE, int HINT>
-__global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
+__device__ __forceinline__ void tile_body(
     const uint64_t* __restrict__ seg_off, const uint64_t* __restrict__ seg_ptr,
     const uint32_t* __restrict__ tile_first_seg, const uint32_t* __restrict__ tab_u_global,
-    uint32_t* __restrict__ partial, uint8_t* __restrict__ chunks, uint64_t* __restrict__ n_bad,
-    TileTables T)
+    uint32_t* __restrict__ partial, uint32_t* __restrict__ acc, uint8_t* __restrict__ chunks,
+    const TileTables& T, const uint32_t* tab, const uint32_t tile, const int lane)
 {
-    __shared__ uint32_t tab[1024];
-    for (int i = threadIdx.x; i < 1024; i += blockDim.x) tab[i] = tab_u_global[i];
-    if (n_bad && blockIdx.x == 0 && threadIdx.x == 0) *n_bad = 0;
-    __syncthreads();
-
-    const int lane = threadIdx.x & (kWaveSize - 1);
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
-    const uint32_t slot = xcd_order(blockIdx.x, gridDim.x, T.xcd_group) * kWavesPerBlock + wave;
-    if (slot >= (T.n_list ? T.n_list : T.n_tiles)) return;
-    const uint32_t tile = T.tile_list ? __builtin_amdgcn_readfirstlane(T.tile_list[slot])
-                                      : T.tile_begin + slot;
-    if (T.skip_bad && __builtin_amdgcn_readfirstlane(T.skip_bad[tile / T.tiles_per_chunk])) return;
     // constant that moves this tile's register to the end of its chunk (tiles per chunk is a
-    // power of two); fetched now, used after the last row
+    // power of two) and supplies the factor x^32 the register lacks; fetched now, used after the
+    // last row
     const uint32_t shift =
         T.tile_shift ? T.tile_shift[((tile & (T.tiles_per_chunk - 1)) + 1) * T.shift_stride - 1] : 0u;
     auto store_register = [&](uint32_t reg) {
         if (T.tile_shift) reg = gf2_mul(reg, shift);
-        if (lane == 0) partial[tile] = reg;
+        if (lane == 0) {
+            if (acc)
+                atomicXor(acc + (tile >> T.tpc_log2), reg);
+            else
+                partial[tile] = reg;
+        }
     };
+    // a pass that only moves bytes (the scatter pass behind a verify pass) folds nothing
+    const bool folding = (acc != nullptr) || (partial != nullptr);
 
     // rows of this tile, as indices into the buffer's rows
     const int64_t g0 = static_cast<int64_t>(tile) * T.tile_rows - T.lead_rows;
@@ -240,7 +239,7 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
                 __builtin_amdgcn_sched_barrier(0);
             }
         });
-        store_register(reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]));
+        if (folding) store_register(reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]));
     };
     // Pack: a default-size tile that the plan found inside one segment starts after a single
     // table read; the segment tables are walked only for the other tiles.  (Restore, whose loads
@@ -419,7 +418,7 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 });
-                store_register(reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]));
+                if (folding) store_register(reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]));
                 return;
             }
         }
@@ -513,10 +512,54 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
         g++;
     }
 
-    store_register(reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]));
+    if (folding) store_register(reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]));
 }
 
-// ---- combine kernels ---------------------------------------------------------------------------
+// Which tile a wavefront takes: position `slot` of the launch is tile tile_begin + slot of the
+// buffer, or, with a chunk list, tile (slot mod tiles per chunk) of the listed chunk
+// slot div tiles per chunk.  The list travels in the kernel arguments, so a call needs no device
+// memory of its own for it.
+template <int MODE, int HINT>
+__global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
+    const uint64_t* __restrict__ seg_off, const uint64_t* __restrict__ seg_ptr,
+    const uint32_t* __restrict__ tile_first_seg, const uint32_t* __restrict__ tab_u_global,
+    uint32_t* __restrict__ partial, uint32_t* __restrict__ acc, uint8_t* __restrict__ chunks,
+    TileTables T)
+{
+    __shared__ uint32_t tab[1024];
+    for (int i = threadIdx.x; i < 1024; i += blockDim.x) tab[i] = tab_u_global[i];
+    __syncthreads();
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
+    const uint32_t slot = xcd_order(blockIdx.x, gridDim.x, T.xcd_group) * kWavesPerBlock + wave;
+    if (slot >= (T.n_list ? T.n_list : T.n_tiles)) return;
+    const uint32_t tile = T.tile_begin + slot;
+    if (T.skip_bad && __builtin_amdgcn_readfirstlane(T.skip_bad[tile >> T.tpc_log2])) return;
+    tile_body<MODE, HINT>(seg_off, seg_ptr, tile_first_seg, tab_u_global, partial, acc, chunks, T, tab,
+                          tile, lane);
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel_listed(
+    const uint64_t* __restrict__ seg_off, const uint64_t* __restrict__ seg_ptr,
+    const uint32_t* __restrict__ tile_first_seg, const uint32_t* __restrict__ tab_u_global,
+    uint32_t* __restrict__ acc, uint8_t* __restrict__ chunks, TileTables T, ChunkList list)
+{
+    __shared__ uint32_t tab[1024];
+    for (int i = threadIdx.x; i < 1024; i += blockDim.x) tab[i] = tab_u_global[i];
+    __syncthreads();
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
+    const uint32_t slot = blockIdx.x * kWavesPerBlock + wave;
+    if (slot >= (list.n << T.tpc_log2)) return;
+    const uint32_t chunk = list.id[slot >> T.tpc_log2];
+    const uint32_t tile = (chunk << T.tpc_log2) + (slot & (T.tiles_per_chunk - 1));
+    if (T.skip_bad && __builtin_amdgcn_readfirstlane(T.skip_bad[chunk])) return;
+    tile_body<MODE, 3>(seg_off, seg_ptr, tile_first_seg, tab_u_global, nullptr, acc, chunks, T, tab,
+                       tile, lane);
+}
+
+// ---- per-chunk kernels around the tiles ---------------------------------------------------------
 
 __device__ __forceinline__ uint32_t chunk_register(const uint32_t* __restrict__ partial,
                                                    uint64_t first, uint32_t n, uint32_t x_tile)
@@ -526,49 +569,59 @@ __device__ __forceinline__ uint32_t chunk_register(const uint32_t* __restrict__ 
     return gf2_mul_const<kX32>(acc);  // the tiles' registers are stored without their factor x^32
 }
 
-// CRC register of a chunk from its tiles' registers, which the tile kernel stored already moved to
-// the chunk end: their XOR, times the factor x^32 that the tiles leave out.  One wavefront, n a
-// power of two, result in every lane.
-__device__ __forceinline__ uint32_t chunk_register_wave(const uint32_t* __restrict__ partial,
-                                                        uint64_t first, uint32_t n, uint32_t lane)
+// Before the tiles: word j of the caller's output array is set to what the tiles' registers of
+// chunk j are XORed into.  Pack: the preset/complement term of a chunk-long CRC, so that the sum
+// is the chunk's CRC32C.  Verify: that term XOR the stored CRC, so that the sum is zero exactly
+// when the recomputed CRC equals the stored one; *n_bad is cleared as well.  The listed forms
+// touch only the chunks named in the list they get as a kernel argument.
+__global__ void preset_kernel(uint32_t* __restrict__ out, const uint32_t* __restrict__ crcs,
+                              uint64_t first, uint64_t n, uint32_t affine,
+                              uint64_t* __restrict__ n_bad)
 {
-    uint32_t acc = 0;
-    for (uint32_t i = lane; i < n; i += kWaveSize) acc ^= partial[first + i];
-#pragma unroll
-    for (int l = 0; l < 6; l++) acc ^= __shfl_xor(acc, 1 << l, kWaveSize);
-    return gf2_mul_const<kX32>(acc);
+    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i == 0 && n_bad) *n_bad = 0;
+    if (i >= n) return;
+    out[first + i] = crcs ? (affine ^ crcs[first + i]) : affine;
 }
 
-constexpr int kCombineWaves = 4;  // chunks per workgroup of the combine kernels
-
-__global__ __launch_bounds__(kWaveSize* kCombineWaves) void combine_pack_kernel(
-    const uint32_t* __restrict__ partial, uint32_t tiles_per_chunk, uint32_t affine,
-    uint64_t n_chunks, uint32_t* __restrict__ crcs)
+__global__ void preset_listed_kernel(uint32_t* __restrict__ out, const uint32_t* __restrict__ crcs,
+                                     uint32_t affine, uint64_t* __restrict__ n_bad, ChunkList list)
 {
-    const uint32_t lane = threadIdx.x & (kWaveSize - 1);
-    const uint64_t j = static_cast<uint64_t>(blockIdx.x) * kCombineWaves + threadIdx.x / kWaveSize;
-    if (j >= n_chunks) return;
-    const uint32_t reg =
-        chunk_register_wave(partial, j * tiles_per_chunk, tiles_per_chunk, lane);
-    if (lane == 0) crcs[j] = reg ^ affine;
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0 && n_bad) *n_bad = 0;
+    if (i >= list.n) return;
+    const uint32_t j = list.id[i];
+    out[j] = crcs ? (affine ^ crcs[j]) : affine;
 }
 
-__global__ __launch_bounds__(kWaveSize* kCombineWaves) void combine_verify_kernel(
-    const uint32_t* __restrict__ partial, uint32_t tiles_per_chunk, uint32_t affine,
-    uint64_t n_chunks, const uint32_t* __restrict__ chunk_list,
-    const uint32_t* __restrict__ crcs, uint32_t* __restrict__ bad, uint64_t* __restrict__ n_bad)
+// After the tiles of a verify pass: bad[j] becomes 0 or 1 and *n_bad counts the ones (one atomic
+// per wavefront that found any).
+__device__ __forceinline__ void finish_one(uint32_t* __restrict__ bad, bool valid, uint64_t j,
+                                           uint64_t* __restrict__ n_bad)
 {
-    const uint32_t lane = threadIdx.x & (kWaveSize - 1);
-    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * kCombineWaves + threadIdx.x / kWaveSize;
-    if (i >= n_chunks) return;
-    const uint64_t j = chunk_list ? chunk_list[i] : i;
-    const uint32_t reg =
-        chunk_register_wave(partial, j * tiles_per_chunk, tiles_per_chunk, lane);
-    if (lane == 0) {
-        const bool is_bad = (reg ^ affine) != crcs[j];
+    bool is_bad = false;
+    if (valid) {
+        is_bad = bad[j] != 0;
         bad[j] = is_bad ? 1u : 0u;
-        if (is_bad) atomicAdd(reinterpret_cast<unsigned long long*>(n_bad), 1ull);
     }
+    const unsigned long long votes = __ballot(is_bad);
+    if (votes && (threadIdx.x & (kWaveSize - 1)) == 0)
+        atomicAdd(reinterpret_cast<unsigned long long*>(n_bad),
+                  static_cast<unsigned long long>(__popcll(votes)));
+}
+
+__global__ void finish_verify_kernel(uint32_t* __restrict__ bad, uint64_t n,
+                                     uint64_t* __restrict__ n_bad)
+{
+    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    finish_one(bad, i < n, i, n_bad);
+}
+
+__global__ void finish_verify_listed_kernel(uint32_t* __restrict__ bad,
+                                            uint64_t* __restrict__ n_bad, ChunkList list)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    finish_one(bad, i < list.n, i < list.n ? list.id[i] : 0u, n_bad);
 }
 
 __global__ void finish_crc_kernel(const uint32_t* __restrict__ partial, uint32_t n_tiles,
@@ -632,11 +685,11 @@ void build_tab_u(uint32_t* tab)
 
 template <int MODE>
 static void launch_tiles_hint(int hint, dim3 grid, dim3 block, hipStream_t stream, const TileTables& t,
-                              uint8_t* c, uint64_t* n_bad)
+                              uint8_t* c)
 {
 #define FF_LAUNCH(H)                                                                             \
     hipLaunchKernelGGL((tile_kernel<MODE, H>), grid, block, 0, stream, t.seg_off, t.seg_ptr,      \
-                       t.tile_first_seg, t.tab_u, t.partial, c, n_bad, t)
+                       t.tile_first_seg, t.tab_u, t.partial, t.acc, c, t)
     switch (hint & 3) {
     case 0: FF_LAUNCH(0); break;
     case 1: FF_LAUNCH(1); break;
@@ -646,42 +699,66 @@ static void launch_tiles_hint(int hint, dim3 grid, dim3 block, hipStream_t strea
 #undef FF_LAUNCH
 }
 
-hipError_t launch_tiles(TileMode mode, const TileTables& t, void* chunks, uint64_t* n_bad,
-                        hipStream_t stream)
+hipError_t launch_tiles(TileMode mode, const TileTables& t, void* chunks, hipStream_t stream,
+                        const ChunkList* list)
 {
-    const uint32_t count = (t.tile_list || t.n_list) ? t.n_list : t.n_tiles;
-    if (count == 0) return hipSuccess;
-    const dim3 grid((count + kWavesPerBlock - 1) / kWavesPerBlock);
     const dim3 block(kWaveSize * kWavesPerBlock);
     uint8_t* c = static_cast<uint8_t*>(chunks);
+    if (list) {
+        // listed chunks (restore and verify only): tiles of the plan's own size, default hints
+        const uint64_t count = static_cast<uint64_t>(list->n) << t.tpc_log2;
+        if (count == 0) return hipSuccess;
+        if (mode == kPack || t.partial || list->n > kMaxListedChunks || count > 0x7FFFFFF0ull)
+            return hipErrorInvalidValue;
+        const dim3 grid(static_cast<unsigned>((count + kWavesPerBlock - 1) / kWavesPerBlock));
+        if (mode == kRestore)
+            hipLaunchKernelGGL((tile_kernel_listed<kRestore>), grid, block, 0, stream, t.seg_off,
+                               t.seg_ptr, t.tile_first_seg, t.tab_u, t.acc, c, t, *list);
+        else
+            hipLaunchKernelGGL((tile_kernel_listed<kVerify>), grid, block, 0, stream, t.seg_off,
+                               t.seg_ptr, t.tile_first_seg, t.tab_u, t.acc, c, t, *list);
+        return hipGetLastError();
+    }
+    const uint32_t count = t.n_list ? t.n_list : t.n_tiles;
+    if (count == 0) return hipSuccess;
+    const dim3 grid((count + kWavesPerBlock - 1) / kWavesPerBlock);
     switch (mode) {
-    case kPack: launch_tiles_hint<kPack>(t.hint, grid, block, stream, t, c, n_bad); break;
-    case kRestore: launch_tiles_hint<kRestore>(t.hint, grid, block, stream, t, c, n_bad); break;
-    case kVerify: launch_tiles_hint<kVerify>(t.hint, grid, block, stream, t, c, n_bad); break;
+    case kPack: launch_tiles_hint<kPack>(t.hint, grid, block, stream, t, c); break;
+    case kRestore: launch_tiles_hint<kRestore>(t.hint, grid, block, stream, t, c); break;
+    case kVerify: launch_tiles_hint<kVerify>(t.hint, grid, block, stream, t, c); break;
     }
     return hipGetLastError();
 }
 
-hipError_t launch_combine_pack(const uint32_t* partial, uint32_t tiles_per_chunk, uint32_t affine,
-                               uint64_t n_chunks, uint32_t* crcs, hipStream_t stream)
+hipError_t launch_preset(uint32_t* out, const uint32_t* crcs, uint64_t first, uint64_t n,
+                         uint32_t affine, uint64_t* n_bad, const ChunkList* list,
+                         hipStream_t stream)
 {
-    const unsigned block = kWaveSize * kCombineWaves;  // one wavefront per chunk
-    const unsigned grid = static_cast<unsigned>((n_chunks + kCombineWaves - 1) / kCombineWaves);
-    hipLaunchKernelGGL(combine_pack_kernel, dim3(grid), dim3(block), 0, stream, partial,
-                       tiles_per_chunk, affine, n_chunks, crcs);
+    const uint64_t count = list ? list->n : n;
+    const unsigned block = 256;
+    unsigned grid = static_cast<unsigned>((count + block - 1) / block);
+    if (grid == 0) grid = 1;  // *n_bad is cleared even when there is no chunk to preset
+    if (list)
+        hipLaunchKernelGGL(preset_listed_kernel, dim3(grid), dim3(block), 0, stream, out, crcs,
+                           affine, n_bad, *list);
+    else
+        hipLaunchKernelGGL(preset_kernel, dim3(grid), dim3(block), 0, stream, out, crcs, first, n,
+                           affine, n_bad);
     return hipGetLastError();
 }
 
-hipError_t launch_combine_verify(const uint32_t* partial, uint32_t tiles_per_chunk,
-                                 uint32_t affine, uint64_t n_chunks,
-                                 const uint32_t* chunk_list, const uint32_t* crcs, uint32_t* bad,
-                                 uint64_t* n_bad, hipStream_t stream)
+hipError_t launch_finish_verify(uint32_t* bad, uint64_t n, uint64_t* n_bad, const ChunkList* list,
+                                hipStream_t stream)
 {
-    if (n_chunks == 0) return hipSuccess;
-    const unsigned block = kWaveSize * kCombineWaves;  // one wavefront per chunk
-    const unsigned grid = static_cast<unsigned>((n_chunks + kCombineWaves - 1) / kCombineWaves);
-    hipLaunchKernelGGL(combine_verify_kernel, dim3(grid), dim3(block), 0, stream, partial,
-                       tiles_per_chunk, affine, n_chunks, chunk_list, crcs, bad, n_bad);
+    const uint64_t count = list ? list->n : n;
+    if (count == 0) return hipSuccess;
+    const unsigned block = 256;
+    const unsigned grid = static_cast<unsigned>((count + block - 1) / block);
+    if (list)
+        hipLaunchKernelGGL(finish_verify_listed_kernel, dim3(grid), dim3(block), 0, stream, bad,
+                           n_bad, *list);
+    else
+        hipLaunchKernelGGL(finish_verify_kernel, dim3(grid), dim3(block), 0, stream, bad, n, n_bad);
     return hipGetLastError();
 }
 

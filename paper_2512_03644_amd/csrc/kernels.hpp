@@ -17,11 +17,16 @@ struct TileTables {
                                               // inside one segment, else 0 (may be absent)
     const uint32_t* tab_u = nullptr;          // [4][256] multiply-by-x^8192 byte tables, then
                                               // [64] lane constants x^(128 * (63 - lane))
-    uint32_t* partial = nullptr;              // [n_tiles] register of every tile run from 0
-    // If set: [plan tiles per chunk] x^(8 * bytes from the end of tile k of a chunk to the end
-    // of the chunk).  A tile's register is multiplied by its entry before it is stored, so that
-    // the registers of a chunk combine by XOR alone.  A pass that folds groups of shift_stride
-    // plan tiles as one uses the entry of the group's last tile.
+    // Where a tile's register goes.  acc set: XORed (atomically) into acc[chunk of the tile], an
+    // array of the caller that launch_preset has prepared; nothing else is written, so calls that
+    // share these tables may overlap in time.  Else partial set: stored to partial[tile] (a
+    // buffer CRC over caller-provided scratch).  Neither: the pass only moves bytes.
+    uint32_t* acc = nullptr;
+    uint32_t* partial = nullptr;
+    // If set: [plan tiles per chunk] x^(32 + 8 * bytes from the end of tile k of a chunk to the
+    // end of the chunk).  A tile's register, which lacks the factor x^32 of a CRC register, is
+    // multiplied by its entry, so that the registers of a chunk combine by XOR alone.  A pass
+    // that folds groups of shift_stride plan tiles as one uses the entry of the group's last tile.
     const uint32_t* tile_shift = nullptr;
     uint32_t shift_stride = 1;
     uint64_t payload = 0;                     // N
@@ -31,12 +36,11 @@ struct TileTables {
     uint32_t lead_rows = 0;                   // rows missing at the front of tile 0
     uint32_t n_tiles = 0;
     uint32_t hint = 3;                        // bit 0: non-temporal tensor-side accesses, bit 1: buffer-side
-    // selective restore
-    const uint32_t* tile_list = nullptr;      // if set: the n_list tiles to process
-    uint32_t n_list = 0;                      // without a list: > 0 selects tiles [tile_begin, +n_list)
+    uint32_t n_list = 0;                      // > 0 selects tiles [tile_begin, tile_begin + n_list)
     uint32_t tile_begin = 0;
     const uint32_t* skip_bad = nullptr;       // if set: bad[] per chunk; tiles of bad chunks are left out
-    uint32_t tiles_per_chunk = 1;
+    uint32_t tiles_per_chunk = 1;             // of this pass (a power of two) ...
+    uint32_t tpc_log2 = 0;                    // ... and its logarithm
     // Workgroups are dealt to the 8 XCDs round-robin.  With xcd_group = G > 0 the workgroups of
     // one XCD take G consecutive groups of tiles, the next XCD the following G, and so on, so
     // that every XCD (and its L2) sweeps runs of G * 128 KiB instead of every eighth 128 KiB.
@@ -45,23 +49,29 @@ struct TileTables {
 
 enum TileMode { kPack = 0, kRestore = 1, kVerify = 2 };
 
+// A list of chunks handed to a kernel by value, inside its arguments: a selective restore needs
+// no device memory of its own for it.  Longer lists are processed in several launches.
+constexpr uint32_t kMaxListedChunks = 254;
+struct ChunkList {
+    uint32_t n = 0;
+    uint32_t id[kMaxListedChunks];
+};
+
 // Folds every tile: kPack gathers segments -> chunks; kRestore reads chunks and scatters to the
-// segments; kVerify only reads chunks.  All three write partial[].  n_bad (may be null) is set
-// to 0 by the kernel so that the verify-combine that follows can add to it.
-hipError_t launch_tiles(TileMode mode, const TileTables& t, void* chunks, uint64_t* n_bad,
-                        hipStream_t stream);
+// segments; kVerify only reads chunks.  With `list` (kRestore / kVerify, registers into t.acc)
+// only the tiles of the listed chunks are processed.
+hipError_t launch_tiles(TileMode mode, const TileTables& t, void* chunks, hipStream_t stream,
+                        const ChunkList* list = nullptr);
 
-// crcs[j] = standard CRC32C of chunk j from its tiles' registers (stored moved to the chunk end,
-// see TileTables::tile_shift).
-hipError_t launch_combine_pack(const uint32_t* partial, uint32_t tiles_per_chunk, uint32_t affine,
-                               uint64_t n_chunks, uint32_t* crcs, hipStream_t stream);
+// out[j] = affine (crcs null: pack) or affine ^ crcs[j] (verify) for chunks [first, first + n), or
+// for the listed chunks; *n_bad = 0 if n_bad is not null.  The tiles then XOR their registers in.
+hipError_t launch_preset(uint32_t* out, const uint32_t* crcs, uint64_t first, uint64_t n,
+                         uint32_t affine, uint64_t* n_bad, const ChunkList* list,
+                         hipStream_t stream);
 
-// bad[j] = (recomputed CRC != crcs[j]); *n_bad += number of bad chunks.  With chunk_list set,
-// only the n_chunks chunks it names are looked at.
-hipError_t launch_combine_verify(const uint32_t* partial, uint32_t tiles_per_chunk,
-                                 uint32_t affine, uint64_t n_chunks,
-                                 const uint32_t* chunk_list, const uint32_t* crcs, uint32_t* bad,
-                                 uint64_t* n_bad, hipStream_t stream);
+// bad[j] = (bad[j] != 0) for chunks [0, n), or for the listed chunks; *n_bad += their number.
+hipError_t launch_finish_verify(uint32_t* bad, uint64_t n, uint64_t* n_bad, const ChunkList* list,
+                                hipStream_t stream);
 
 // CRC of one buffer: combine n_tiles registers, then run the register over `tail_bytes` more
 // bytes at `tail`, then apply the preset/complement term `affine`.

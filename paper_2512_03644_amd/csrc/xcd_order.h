@@ -14,7 +14,7 @@ namespace ffsnap {
 // Workgroups are dealt to the 8 XCDs round-robin by launch index.  Within every complete round
 // of 8 * g workgroups, workgroup b takes position (b mod 8) * g + b div 8 of the round, so the
 // g workgroups that land on one XCD take g consecutive positions.  A bijection on [0, n);
-// the identity when g == 0 and on the incomplete last round.
+// the identity when g == 0 and on the incomplete last round.  g <= 2^28, so that 8 * g fits.
 FF_XCD_HD inline uint32_t xcd_order(uint32_t b, uint32_t n, uint32_t g)
 {
     constexpr uint32_t kXcds = 8;

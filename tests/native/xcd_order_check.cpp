@@ -6,7 +6,8 @@
 using ffsnap::xcd_order;
 int main()
 {
-    const uint32_t gs[] = {0, 1, 2, 3, 4, 8, 16, 100, 1u << 20};
+    // 2^28 is the longest run the plan flags can ask for: 8 * g still fits 32 bits
+    const uint32_t gs[] = {0, 1, 2, 3, 4, 8, 16, 100, 1u << 20, 1u << 28};
     for (uint32_t g : gs) {
         for (uint32_t n = 0; n <= 700; n++) {
             std::vector<int> seen(n, 0);

@@ -316,9 +316,77 @@ def test_copy_ceiling_copies_exactly(nbytes):
     assert bool((dst[:64] == 0xA5).all()) and bool((dst[64 + nbytes:] == 0xA5).all())
 
 
+def test_one_plan_on_two_streams_at_once(oracle):
+    """A plan is immutable: calls on ONE plan may overlap in time as long as their outputs differ.
+    Two streams pack the same shard into two buffers and verify them concurrently, several times
+    over (once with a corrupted chunk each); every result equals the oracle's."""
+    shard = wl.param_shard("s", [1300000, 70001, 333, 250000], 1 << 18, 41, DEV, tiny_recipe=True)
+    plan = ff.plan_for_shard(shard)
+    want_buf, want_crcs = oracle.pack(_host_segments(shard)[0], shard.chunk_bytes, threads=8)
+    outs = [ff.alloc_outputs(plan, DEV) for _ in range(2)]
+    streams = [torch.cuda.Stream() for _ in range(2)]
+    for st in streams:
+        st.wait_stream(torch.cuda.current_stream())
+    dirty = []
+    for rep in range(6):
+        for k, ((chunks, crcs, bad, n_bad), st) in enumerate(zip(outs, streams)):
+            if rep == 3:      # corrupt one chunk of each buffer between two rounds, in stream order
+                with torch.cuda.stream(st):
+                    chunks[(5 + k) * shard.chunk_bytes + 17] ^= 0x40
+                ff.ff_restore(plan, chunks, crcs, bad, n_bad, flags=ff.FF_RESTORE_VERIFY_ONLY,
+                              stream=st)
+                with torch.cuda.stream(st):
+                    dirty.append((bad.clone(), n_bad.clone()))
+            ff.ff_pack(plan, chunks, crcs, stream=st)
+            ff.ff_restore(plan, chunks, crcs, bad, n_bad, flags=ff.FF_RESTORE_VERIFY_ONLY, stream=st)
+    for st in streams:
+        st.synchronize()
+    for k, (chunks, crcs, bad, n_bad) in enumerate(outs):
+        assert np.array_equal(chunks.cpu().numpy(), want_buf)
+        assert np.array_equal(_u32(crcs), want_crcs)
+        assert int(n_bad.item()) == 0 and not bool(bad.any())
+        dbad, dn = dirty[k]
+        assert int(dn.item()) == 1 and torch.nonzero(dbad).flatten().tolist() == [5 + k]
+
+
+def test_one_plan_two_host_threads(oracle):
+    """The same from two host threads, each with its own stream and outputs, sharing the plan."""
+    import threading
+    shard = wl.param_shard("t", [900000, 12345, 400001], 1 << 17, 43, DEV, tiny_recipe=True)
+    plan = ff.plan_for_shard(shard)
+    want_buf, want_crcs = oracle.pack(_host_segments(shard)[0], shard.chunk_bytes, threads=8)
+    outs = [ff.alloc_outputs(plan, DEV) for _ in range(2)]
+    streams = [torch.cuda.Stream() for _ in range(2)]
+    for st in streams:
+        st.wait_stream(torch.cuda.current_stream())
+    errors = []
+
+    def worker(k):
+        try:
+            torch.cuda.set_device(0)
+            chunks, crcs, bad, n_bad = outs[k]
+            for _ in range(8):
+                ff.ff_pack(plan, chunks, crcs, stream=streams[k])
+                ff.ff_restore(plan, chunks, crcs, bad, n_bad, flags=ff.FF_RESTORE_VERIFY_ONLY,
+                              stream=streams[k])
+            streams[k].synchronize()
+        except Exception as e:          # surfaced in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for chunks, crcs, bad, n_bad in outs:
+        assert np.array_equal(chunks.cpu().numpy(), want_buf)
+        assert np.array_equal(_u32(crcs), want_crcs) and int(n_bad.item()) == 0
+
+
 def test_two_plans_on_two_streams_at_once(oracle):
-    """One plan per stream is the rule for work that overlaps in time: two shards packed and
-    verified concurrently, each through its own plan, stream and buffers, several times over."""
+    """Two shards packed and verified concurrently, each through its own plan, stream and
+    buffers, several times over."""
     shards = [wl.param_shard("s%d" % k, [300000 + 7 * k, 70001, 333], 1 << 18, 40 + k, DEV,
                              tiny_recipe=True) for k in range(2)]
     plans = [ff.plan_for_shard(s) for s in shards]
@@ -421,6 +489,13 @@ def test_fused_adam_many_random_sizes(oracle):
     _adam_and_compare(oracle, numels, 8192, seed=42)
 
 
+def test_fused_adam_more_groups_than_one_launch_carries(oracle):
+    # the gradient pointers travel in kernel arguments, 384 groups per launch: 1000 groups take
+    # three launches, the last one partly filled
+    numels = [int(x) for x in np.random.default_rng(43).integers(1, 700, size=1000)]
+    _adam_and_compare(oracle, numels, 4096, seed=43)
+
+
 @pytest.mark.parametrize("step", [1, 2, 1000])
 def test_fused_adam_steps_and_hparams(oracle, step):
     hp = dict(lr=1e-3, beta1=0.8, beta2=0.999, eps=1e-6, weight_decay=0.0, step=step)
@@ -453,22 +528,22 @@ def test_fused_adam_special_values(oracle):
     chunks, crcs, _, _ = ff.alloc_outputs(plan, DEV)
     ff.ff_adam_step_snapshot(plan, [p.grad], HP, chunks, crcs)
     torch.cuda.synchronize()
-    oracle.adam_snapshot(params_np, grads_np, host, 4096, HP)
-    # A NaN result is correct whatever its sign and payload (IEEE 754 leaves both open, and the
-    # CPU's subtract and the GPU's add-of-negated differ in the sign they give): compare what is
-    # unique -- every non-NaN value bit for bit, and NaN-ness position by position.
+    want_buf, want_crcs = oracle.adam_snapshot(params_np, grads_np, host, 4096, HP)
+    # A NaN result is stored as the canonical quiet NaN by both sides, so state, snapshot and CRCs
+    # are compared byte for byte like everything else.
     n_nan = 0
     for got_t, want, bits in ((p.w16, params_np[0][0], 16), (p.master, params_np[0][1], 32),
                               (p.m, params_np[0][2], 32), (p.v, params_np[0][3], 32)):
         got = wl.to_numpy_bytes(got_t).view(np.uint16 if bits == 16 else np.uint32)
         want = want.view(got.dtype)
+        assert np.array_equal(got, want)
         emask, fmask = (0x7F80, 0x007F) if bits == 16 else (0x7F800000, 0x007FFFFF)
-        nan_g = ((got & emask) == emask) & ((got & fmask) != 0)
-        nan_w = ((want & emask) == emask) & ((want & fmask) != 0)
-        assert np.array_equal(nan_g, nan_w)
-        n_nan += int(nan_w.sum())
-        assert np.array_equal(got[~nan_w], want[~nan_w])
+        nan = ((got & emask) == emask) & ((got & fmask) != 0)
+        n_nan += int(nan.sum())
+        assert bool((got[nan] == (0x7FC0 if bits == 16 else 0x7FC00000)).all())
     assert n_nan >= 3
+    assert np.array_equal(chunks.cpu().numpy(), want_buf)
+    assert np.array_equal(_u32(crcs), want_crcs)
     # and the snapshot is the packed image of the state the GPU left in place
     chunks2, crcs2, _, _ = ff.alloc_outputs(plan, DEV)
     ff.ff_pack(plan, chunks2, crcs2)
@@ -492,8 +567,8 @@ def test_fused_adam_argument_errors():
 
 
 def test_fused_adam_consecutive_steps_and_new_gradient_buffers(oracle):
-    """Three steps on one plan: the same gradient buffers twice (their pointers are uploaded once),
-    then different buffers.  The oracle takes the same three steps."""
+    """Three steps on one plan: the same gradient buffers twice, then different buffers (the
+    pointers travel with every call).  The oracle takes the same three steps."""
     numels = [3000, 70001, 255]
     shard = wl.param_shard("a", numels, 4096, 21, DEV, with_grads=True)
     plan = ff.plan_for_shard(shard)
@@ -521,9 +596,9 @@ def test_fused_adam_consecutive_steps_and_new_gradient_buffers(oracle):
             assert np.array_equal(wl.to_numpy_bytes(t), h), step
 
 def test_hip_graph_replays_of_the_whole_step():
-    """The device entry points only launch kernels (the fused step uploads its gradient pointers
-    on the first call alone), so a step can be captured into a HIP graph.  Every replay, with
-    eager work between replays, must equal the eager result."""
+    """The device entry points only launch kernels (the gradient pointers of the fused step are
+    kernel arguments), so a step can be captured into a HIP graph.  Every replay, with eager work
+    between replays, must equal the eager result."""
     numels = [3000, 70001, 255, 40000]
     shard = wl.param_shard("a", numels, 1 << 16, 33, DEV, with_grads=True)
     plan = ff.plan_for_shard(shard)
@@ -536,7 +611,7 @@ def test_hip_graph_replays_of_the_whole_step():
         ff.ff_pack(plan, pk, pcrcs)
         ff.ff_restore(plan, chunks, crcs, bad, n_bad)
 
-    step()                                           # eager once: uploads the pointer table
+    step()                                           # warm-up: the first launch loads the kernels
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
@@ -581,7 +656,7 @@ def test_hip_graph_replays_of_two_chained_steps():
         ff.ff_adam_step_chained(plan, grads, HP, b, a, crcs_a)
 
     start = a.clone()
-    two_steps()                                      # eager once: uploads the pointer table
+    two_steps()                                      # warm-up: the first launch loads the kernels
     torch.cuda.synchronize()
     a.copy_(start)
     graph = torch.cuda.CUDAGraph()
@@ -864,20 +939,22 @@ def test_fused_adam_f16_nonfinite_gradients_and_weight_overflow(oracle):
     ff.ff_adam_step_snapshot_f16(plan, [q.grad for q in shard.params], HP, inv, n_nonfinite,
                                  chunks, crcs)
     torch.cuda.synchronize()
-    _, _, want_bad = oracle.adam_snapshot_f16(params_np, grads_np, inv, host, 4096, HP)
+    want_buf, want_crcs, want_bad = oracle.adam_snapshot_f16(params_np, grads_np, inv, host, 4096, HP)
     assert want_bad == 5 and int(n_nonfinite.item()) == 5
-    # NaN results: compare NaN-ness (sign and payload of a NaN result are not fixed by IEEE 754);
-    # everything else bit for bit
+    # NaN results are stored in the canonical form on both sides: everything bit for bit
+    n_nan = 0
     for q, (w16, master, m, v) in zip(shard.params, params_np):
         for got_t, want in ((q.master, master), (q.m, m), (q.v, v)):
             got = got_t.cpu().numpy()
-            nan = np.isnan(want)
-            assert np.array_equal(np.isnan(got), nan)
-            assert np.array_equal(got.view(np.uint32)[~nan], want.view(np.uint32)[~nan])
+            assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+            assert bool((got.view(np.uint32)[np.isnan(got)] == 0x7FC00000).all())
+            n_nan += int(np.isnan(got).sum())
         got_w = wl.to_numpy_bytes(q.w16).view(np.uint16)
-        nan_w = np.isnan(w16.view(np.float16))
-        assert np.array_equal(np.isnan(got_w.view(np.float16)), nan_w)
-        assert np.array_equal(got_w[~nan_w], w16[~nan_w])
+        assert np.array_equal(got_w, w16)
+        assert bool((got_w[np.isnan(got_w.view(np.float16))] == 0x7E00).all())
+    assert n_nan >= 3
+    assert np.array_equal(chunks.cpu().numpy(), want_buf)
+    assert np.array_equal(_u32(crcs), want_crcs)
     w = wl.to_numpy_bytes(p.w16).view(np.uint16)
     assert w[11] == 0x7C00 and w[12] == 0xFC00 and w[15] == 0x7C00     # overflow to infinity
     assert w[10] == 0x7BFF                                             # 65519 * decay stays finite
@@ -961,6 +1038,118 @@ def test_restore_chunks_matches_oracle(oracle, chunk, tile_log2):
                                bad.data_ptr(), n_bad.data_ptr(), 0, None) == ff.FF_ERR_INVALID
 
 
+@pytest.mark.parametrize("flags", [0, ff.FF_RESTORE_SKIP_BAD, ff.FF_RESTORE_VERIFY_ONLY])
+def test_restore_chunks_long_list(oracle, flags):
+    """A list longer than one launch carries in its arguments (several launches per call): 700
+    of 1000 chunks, some of them corrupt, against the oracle."""
+    chunk = 1024
+    numels = [int(x) for x in np.random.default_rng(77).integers(100, 30000, size=18)]
+    shard = wl.param_shard("long", numels, chunk, 33, DEV, tiny_recipe=True)
+    plan, chunks, crcs, bad, n_bad, want_buf, want_crcs = _pack_and_compare(shard, oracle)
+    n = plan.num_chunks
+    assert n > 900
+    rng = np.random.default_rng(8)
+    ids = sorted({int(x) for x in rng.choice(n, size=700, replace=False)})
+    dirty = chunks.clone()
+    flipped = [ids[3], ids[260], ids[511], ids[699]]          # first, middle and last launch
+    for j in flipped:
+        dirty[j * chunk + (j % 1000)] ^= 0x08
+    _poison_segments(shard)
+    bad.fill_(7)
+    n_bad.fill_(99)
+    ff.ff_restore_chunks(plan, dirty, crcs, ids, bad, n_bad, flags=flags)
+    torch.cuda.synchronize()
+    host = [np.full(h.size, 0xA5, dtype=np.uint8) for h in _host_segments(shard)[0]]
+    want_bad = np.full(n, 7, dtype=np.uint32)
+    if flags == ff.FF_RESTORE_VERIFY_ONLY:
+        vb, _ = oracle.verify(dirty.cpu().numpy(), want_crcs, chunk)
+        want_bad[ids] = vb[ids]
+        want_n = int(vb[ids].sum())
+    else:
+        want_n = oracle.restore_chunks(host, chunk, dirty.cpu().numpy(), want_crcs, ids, want_bad,
+                                       skip_bad=flags == ff.FF_RESTORE_SKIP_BAD)
+    assert want_n == len(flipped) == int(n_bad.item())
+    assert np.array_equal(_u32(bad), want_bad)
+    assert np.array_equal(_segments_as_stream(shard), np.concatenate(host))
+
+
+def test_swapped_chunks_are_both_flagged(oracle):
+    """Chunk reorder on the way to the receiver: two chunks of the buffer change places while the
+    CRC array keeps its order.  Exactly those two are flagged (their contents differ), by the
+    oracle and by ff_restore alike; swapping the CRCs along makes the buffer verify again but
+    it is then a different snapshot, which the byte comparison shows."""
+    numels = [int(x) for x in np.random.default_rng(6).integers(1000, 90000, size=30)]
+    shard = wl.param_shard("swap", numels, 1 << 16, 6, DEV, tiny_recipe=True)
+    plan, chunks, crcs, bad, n_bad, want_buf, want_crcs = _pack_and_compare(shard, oracle)
+    C, n = shard.chunk_bytes, plan.num_chunks
+    a, b = 2, n - 3
+    assert want_crcs[a] != want_crcs[b]
+    moved = chunks.clone()
+    moved[a * C:(a + 1) * C] = chunks[b * C:(b + 1) * C]
+    moved[b * C:(b + 1) * C] = chunks[a * C:(a + 1) * C]
+    for flags in (0, ff.FF_RESTORE_VERIFY_ONLY, ff.FF_RESTORE_SKIP_BAD):
+        _poison_segments(shard)
+        ff.ff_restore(plan, moved, crcs, bad, n_bad, flags=flags)
+        torch.cuda.synchronize()
+        want_bad, want_n = oracle.verify(moved.cpu().numpy(), want_crcs, C)
+        assert want_n == 2 and list(np.nonzero(want_bad)[0]) == [a, b]
+        assert int(n_bad.item()) == 2 and np.array_equal(_u32(bad), want_bad)
+    # the skip-bad pass left the two chunks' tensor ranges untouched and loaded the rest
+    got = _segments_as_stream(shard)
+    for j in range(n):
+        lo, hi = j * C, min((j + 1) * C, got.size)
+        if j in (a, b):
+            assert bool((got[lo:hi] == 0xA5).all())
+        else:
+            assert np.array_equal(got[lo:hi], want_buf[lo:hi])
+    crcs_moved = crcs.clone()
+    crcs_moved[a], crcs_moved[b] = crcs[b], crcs[a]
+    ff.ff_restore(plan, moved, crcs_moved, bad, n_bad, flags=ff.FF_RESTORE_VERIFY_ONLY)
+    torch.cuda.synchronize()
+    assert int(n_bad.item()) == 0
+
+
+def test_restore_checked_refuses_another_layout(oracle):
+    """A buffer packed for one layout offered to a plan with another one: ff_restore_checked
+    returns FF_ERR_LAYOUT and writes nothing -- no tensor byte, no bad[], no n_bad; with the
+    matching id it is ff_restore."""
+    numels = [30000, 70001, 4096]
+    C = 1 << 15
+    sender = wl.param_shard("snd", numels, C, 3, DEV, tiny_recipe=True)
+    plan_s, chunks, crcs, bad, n_bad, want_buf, want_crcs = _pack_and_compare(sender, oracle)
+    # receivers: same sizes in another order; one element more; another chunk size
+    others = [wl.param_shard("r1", [70001, 30000, 4096], C, 4, DEV, tiny_recipe=True),
+              wl.param_shard("r2", [30000, 70001, 4097], C, 4, DEV, tiny_recipe=True),
+              wl.param_shard("r3", numels, 2 * C, 4, DEV, tiny_recipe=True)]
+    for recv in others:
+        plan_r = ff.plan_for_shard(recv)
+        assert plan_r.layout_id != plan_s.layout_id
+        _poison_segments(recv)
+        n_r = plan_r.num_chunks
+        bad_r = torch.full((max(n_r, plan_s.num_chunks),), 7, dtype=torch.int32, device=DEV)
+        n_bad.fill_(99)
+        big = torch.zeros(max(plan_r.buffer_bytes, plan_s.buffer_bytes), dtype=torch.uint8, device=DEV)
+        big[:plan_s.buffer_bytes] = chunks
+        crcs_r = torch.zeros(max(n_r, plan_s.num_chunks), dtype=torch.int32, device=DEV)
+        crcs_r[:plan_s.num_chunks] = crcs
+        with pytest.raises(ff.FFError) as e:
+            ff.ff_restore_checked(plan_r, plan_s.layout_id, big, crcs_r, bad_r, n_bad)
+        assert e.value.status == ff.FF_ERR_LAYOUT
+        torch.cuda.synchronize()
+        assert all(bool((t.view(torch.uint8) == 0xA5).all()) for t in recv.segments)
+        assert bool((bad_r == 7).all()) and int(n_bad.item()) == 99
+    # a receiver with the sender's layout (fresh tensors, other addresses) loads the state
+    recv = wl.param_shard("r0", numels, C, 9, DEV, tiny_recipe=True)
+    plan_r = ff.plan_for_shard(recv)
+    assert plan_r.layout_id == plan_s.layout_id
+    _poison_segments(recv)
+    ff.ff_restore_checked(plan_r, plan_s.layout_id, chunks, crcs, bad, n_bad)
+    torch.cuda.synchronize()
+    assert int(n_bad.item()) == 0
+    got = _segments_as_stream(recv)
+    assert np.array_equal(got, want_buf[:got.size])
+
+
 def test_full_restore_skip_bad_on_ragged_layout(oracle):
     lay = wl.fragmented_layout(seed=4, n_tensors=1500, mu=6.0, sigma=2.0, max_numel=1 << 16)
     shard = wl.fragmented_shard(lay, 1 << 14, seed=4, device=DEV)
@@ -1040,7 +1229,8 @@ def test_failover_scenario(oracle):
     for j in damaged:
         received[j * C + 100 + j] ^= 0x10
     _, _, bad, n_bad = ff.alloc_outputs(plan_n, DEV)
-    ff.ff_restore(plan_n, received, crcs, bad, n_bad, flags=ff.FF_RESTORE_SKIP_BAD)
+    ff.ff_restore_checked(plan_n, plan.layout_id, received, crcs, bad, n_bad,
+                          flags=ff.FF_RESTORE_SKIP_BAD)
     torch.cuda.synchronize()
     again = torch.nonzero(bad).flatten().tolist()
     assert again == damaged and int(n_bad.item()) == len(damaged)

@@ -76,6 +76,11 @@ def test_argument_validation():
     assert plan_status(None, 1, 1024) == ff.FF_ERR_NULL
     assert L.ff_snapshot_plan(segs, 1, 1024, H, None) == ff.FF_ERR_NULL
     assert plan_status(segs, 1, 1024, H | 2) == ff.FF_ERR_INVALID    # unknown flag
+    # XCD run lengths: 2^28 workgroups per XCD is the longest a 32-bit launch index allows
+    assert plan_status(segs, 1, 1024, H | ff.FF_PLAN_XCD_ORDER(30)) == ff.FF_ERR_INVALID
+    for n in (1, 4, 29, 31):
+        assert plan_status(segs, 1, 1024, H | ff.FF_PLAN_XCD_ORDER(n)) == ff.FF_OK
+        L.ff_plan_destroy(out)
     assert plan_status(segs, 0, 1024) == ff.FF_ERR_EMPTY
     empty = ff.make_segments([torch.zeros(0)])
     assert plan_status(empty, 1, 1024) == ff.FF_ERR_EMPTY

@@ -109,6 +109,70 @@ def test_special_cases(oracle):
     assert np.array_equal(p, master * decay)
 
 
+@pytest.mark.parametrize("fp16", [False, True])
+def test_nan_results_take_the_canonical_form(oracle, fp16):
+    """A new master, m or v that is NaN is stored as 0x7FC00000 whatever the sign and payload of
+    the NaN that went in or that the arithmetic produced, the 16-bit weight is rounded from that
+    (bf16 0x7FC0, fp16 0x7E00); NaN-ness itself is the arithmetic's (checked against float64),
+    and every other element is what the step gives without the rule."""
+    n = 64
+    master, m, v, g16 = _draw(n, 5)
+    u = lambda bits: np.array([bits], dtype=np.uint32).view(np.float32)[0]
+    # NaNs of either sign with payloads, in each input; inf - inf and 0 * inf produced inside
+    m[0], m[1] = u(0x7FC12345), u(0xFFFFFFFF)          # quiet +, quiet - with full payload
+    v[2] = u(0xFF800001)                               # signalling, negative
+    master[3], master[4] = u(0xFFC00000), u(0x7F800123)
+    v[5] = -1.0                                        # sqrt of a negative number
+    master[6], m[6] = np.float32(np.inf), np.float32(np.inf)      # inf - inf in the last line
+    gbits = _bits(g16)
+    g_f32 = g16.to(torch.float32).numpy()
+    if fp16:
+        gbits = torch.from_numpy(g_f32).to(torch.float16).view(torch.int16).numpy().view(np.uint16).copy()
+        g_f32 = torch.from_numpy(gbits.view(np.int16)).view(torch.float16).to(torch.float32).numpy()
+        gbits[7] = 0xFE01                              # a NaN gradient
+        g_f32[7] = np.nan
+    ref = [x.copy() for x in (master, m, v)]
+    w16 = np.zeros(n, dtype=np.uint16)
+    if fp16:
+        oracle.adam_f32_f16(gbits, 1.0, master, m, v, w16, **HP)
+    else:
+        oracle.adam_f32(gbits, master, m, v, w16, **HP)
+    # NaN-ness per element from the same formulas in float64 (numpy)
+    hp = {k: (float(np.float32(x)) if k != "step" else x) for k, x in HP.items()}
+    with np.errstate(all="ignore"):
+        P, M, V = (x.astype(np.float64) for x in ref)
+        g = g_f32.astype(np.float64)
+        m1 = hp["beta1"] * M + (1 - hp["beta1"]) * g
+        v1 = hp["beta2"] * V + (1 - hp["beta2"]) * g * g
+        d = np.sqrt(v1) / np.sqrt(1 - hp["beta2"] ** hp["step"]) + hp["eps"]
+        p1 = P * (1 - hp["lr"] * hp["weight_decay"]) - hp["lr"] / (1 - hp["beta1"] ** hp["step"]) * (m1 / d)
+    n_nan = 0
+    for got, want in ((master, p1), (m, m1), (v, v1)):
+        bits = got.view(np.uint32)
+        nan = np.isnan(want)
+        assert np.array_equal(np.isnan(got), nan)
+        assert bool((bits[nan] == 0x7FC00000).all())
+        n_nan += int(nan.sum())
+    assert n_nan >= (12 if fp16 else 9)
+    assert bool((w16[np.isnan(p1)] == (0x7E00 if fp16 else 0x7FC0)).all())
+    # the elements without any NaN: the same values as a run whose NaN sources are replaced
+    clean = ~(np.isnan(p1) | np.isnan(m1) | np.isnan(v1))
+    assert clean.sum() >= n - 8
+    a, b, c = (x.copy() for x in ref)
+    for arr in (a, b, c):
+        arr[~clean] = 1.0
+    gb = gbits.copy()
+    gb[~clean] = 0
+    w2 = np.zeros(n, dtype=np.uint16)
+    if fp16:
+        oracle.adam_f32_f16(gb, 1.0, a, b, c, w2, **HP)
+    else:
+        oracle.adam_f32(gb, a, b, c, w2, **HP)
+    for got, other in ((master, a), (m, b), (v, c)):
+        assert np.array_equal(got.view(np.uint32)[clean], other.view(np.uint32)[clean])
+    assert np.array_equal(w16[clean], w2[clean])
+
+
 def test_bf16_weight_is_rne_of_the_new_master(oracle):
     n = 5000
     master, m, v, g16 = _draw(n, 51)
