@@ -327,6 +327,19 @@ int restore_impl(const ff_plan* p, const void* chunks, const uint32_t* crcs, uin
     void* buf = const_cast<void*>(chunks);
     const bool verify_only = (flags & FF_RESTORE_VERIFY_ONLY) != 0;
     const bool skip_bad = (flags & FF_RESTORE_SKIP_BAD) != 0;
+    if ((verify_only || skip_bad) && !list && verify_chunks_applicable(L.chunk_bytes, L.n_chunks) &&
+        L.tile_bytes <= L.chunk_bytes / 8 && L.tile_bytes <= (1u << 16) &&
+        (1u << 16) % L.tile_bytes == 0) {
+        // pass 1 over a whole buffer of many chunks: one workgroup per chunk
+        FF_HIP_TRY(launch_verify_chunks(t, L.chunk_bytes, static_cast<uint32_t>(L.tile_bytes),
+                                        L.tiles_per_chunk, p->affine, buf, crcs, bad, n_bad,
+                                        L.n_chunks, s));
+        if (verify_only) return FF_OK;
+        t.acc = nullptr;
+        t.skip_bad = bad;
+        FF_HIP_TRY(launch_tiles(kRestore, t, buf, s, nullptr));
+        return FF_OK;
+    }
     FF_HIP_TRY(launch_preset(bad, crcs, 0, L.n_chunks, p->affine, clear_n_bad ? n_bad : nullptr, list, s));
     if (verify_only || skip_bad) {
         // pass 1: read and fold only; over the whole buffer it runs on grouped tiles

@@ -39,7 +39,7 @@ constexpr int kDepth = 8;  // rows in flight per wavefront
 // deeper queue: with no loop there is no loop-carried register to copy and no wait for all
 // outstanding loads at a loop head.
 constexpr int kWholeRows = 32;   // rows of a default (32 KiB) tile
-constexpr int kVerifyRows = 64;  // rows of a read-only pass's grouped (64 KiB) tile
+constexpr int kVerifyRows = 64;  // a read-only pass walks its grouped tile in blocks of 64 rows
 // rows requested before the first store on that path (measured: 16 is best when the stores go to
 // the chunk buffer, the whole tile when they go to the tensors)
 template <int MODE>
@@ -217,7 +217,7 @@ __device__ __forceinline__ void tile_body(
     static_for<kNE>([&](auto e) { static_for<kNF>([&](auto f) { S[e][f] = 0; }); });
 
     // Whole-tile paths: all rows real and, on the tensor side, inside one segment.
-    auto whole_tile = [&](auto rows_c, auto depth_c, const uint8_t* bp, const uint8_t* tp) {
+    auto whole_rows = [&](auto rows_c, auto depth_c, const uint8_t* bp, const uint8_t* tp) {
         constexpr int kRows = rows_c, kD = depth_c;
         static_assert(kRows % kNE == 0 && kD <= kRows, "whole-tile path");
         auto fetch = [&](int r) {
@@ -239,6 +239,9 @@ __device__ __forceinline__ void tile_body(
                 __builtin_amdgcn_sched_barrier(0);
             }
         });
+    };
+    auto whole_tile = [&](auto rows_c, auto depth_c, const uint8_t* bp, const uint8_t* tp) {
+        whole_rows(rows_c, depth_c, bp, tp);
         if (folding) store_register(reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]));
     };
     // Pack: a default-size tile that the plan found inside one segment starts after a single
@@ -310,9 +313,16 @@ __device__ __forceinline__ void tile_body(
                 return;
             }
         }
-        if (MODE == kVerify && T.tile_rows == kVerifyRows) {
-            whole_tile(std::integral_constant<int, kVerifyRows>{},
-                       std::integral_constant<int, kWholeDepth<kVerify>>{}, bp, tp);
+        if (MODE == kVerify && T.tile_rows % kVerifyRows == 0) {
+            // a read-only pass folds a long tile as one message, block after block (a block is a
+            // whole number of rotations of the state); one reduction and one atomic per tile
+            const int blocks = static_cast<int>(T.tile_rows) / kVerifyRows;
+            for (int blk = 0; blk < blocks; blk++) {
+                whole_rows(std::integral_constant<int, kVerifyRows>{},
+                           std::integral_constant<int, kWholeDepth<kVerify>>{}, bp, tp);
+                bp += kVerifyRows * kRowBytes;
+            }
+            if (folding) store_register(reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]));
             return;
         }
         // Piecewise path: a default-size tile that starts inside the payload and touches at most
@@ -639,6 +649,62 @@ __global__ void finish_crc_kernel(const uint32_t* __restrict__ partial, uint32_t
 
 __global__ void zero_u64_kernel(uint64_t* p) { *p = 0; }
 
+// Verify pass over a whole buffer, one workgroup per chunk: wavefront w folds the w-th of WAVES
+// equal shares of the chunk as one message (blocks of kVerifyRows rows, straight-line), the
+// shares' registers meet in LDS, and one lane compares the chunk's CRC32C with the stored one and
+// writes bad[j].  No atomics on the per-chunk words and no kernels before or after it (a tile's
+// register delivered by an atomic keeps its wavefront waiting for the acknowledgement, which a pass
+// without stores to wait for anyway pays in full); *n_bad must be zero at launch and is touched
+// for bad chunks only.  share_shift[w] = x^(32 + 8 * bytes behind share w in the chunk).
+template <int WAVES, bool NT>
+__global__ __launch_bounds__(kWaveSize * WAVES) void verify_chunk_kernel(
+    const uint8_t* __restrict__ chunks, const uint32_t* __restrict__ tab_u_global,
+    const uint32_t* __restrict__ tile_shift, uint32_t tiles_per_share, uint32_t blocks_per_share,
+    uint64_t chunk_bytes, uint32_t affine, const uint32_t* __restrict__ crcs,
+    uint32_t* __restrict__ bad, uint64_t* __restrict__ n_bad)
+{
+    __shared__ uint32_t tab[1024];
+    __shared__ uint32_t regs[WAVES];
+    for (int i = threadIdx.x; i < 1024; i += blockDim.x) tab[i] = tab_u_global[i];
+    __syncthreads();
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
+    const uint64_t j = blockIdx.x;
+    const uint32_t shift = tile_shift[(wave + 1) * tiles_per_share - 1];
+    const uint8_t* bp = chunks + j * chunk_bytes +
+                        static_cast<uint64_t>(wave) * blocks_per_share * (kVerifyRows * kRowBytes) +
+                        16u * lane;
+    uint32_t S[kNE][kNF];
+    static_for<kNE>([&](auto e) { static_for<kNF>([&](auto f) { S[e][f] = 0; }); });
+    constexpr int kD = kWholeDepth<kVerify>;
+    for (uint32_t blk = 0; blk < blocks_per_share; blk++) {
+        u32x4 w[kD];
+        static_for<kD>([&](auto k) { w[k] = load16_stream<NT>(bp + k * kRowBytes); });
+        static_for<kVerifyRows>([&](auto Jc) {
+            constexpr int J = Jc;
+            const u32x4 x = w[J % kD];
+            fold_word<J % kNE>(S, x);
+            if constexpr (J + kD < kVerifyRows) {
+                __builtin_amdgcn_sched_barrier(0);
+                w[J % kD] = load16_stream<NT>(bp + (J + kD) * kRowBytes);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+        bp += kVerifyRows * kRowBytes;
+    }
+    const uint32_t reg = gf2_mul(reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]), shift);
+    if (lane == 0) regs[wave] = reg;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t crc = affine;
+#pragma unroll
+        for (int w = 0; w < WAVES; w++) crc ^= regs[w];
+        const bool is_bad = crc != crcs[j];
+        bad[j] = is_bad ? 1u : 0u;
+        if (is_bad) atomicAdd(reinterpret_cast<unsigned long long*>(n_bad), 1ull);
+    }
+}
+
 // Plain copy in the tile kernel's access pattern, without the CRC: 32 KiB per wavefront with 16
 // rows in flight, 4 wavefronts per workgroup on adjacent tiles, XCD-aware order.  The reference
 // that pack and restore are measured against.  n16 counts 16-byte units.
@@ -768,6 +834,45 @@ hipError_t launch_finish_crc(const uint32_t* partial, uint32_t n_tiles, uint32_t
 {
     hipLaunchKernelGGL(finish_crc_kernel, dim3(1), dim3(64), 0, stream, partial, n_tiles, x_tile,
                        tail, tail_bytes, affine, out);
+    return hipGetLastError();
+}
+
+bool verify_chunks_applicable(uint64_t chunk_bytes, uint64_t n_chunks)
+{
+    // every wavefront needs whole 64 KiB blocks, and the launch enough wavefronts to fill the chip
+    return chunk_bytes >= 4ull * kVerifyRows * kRowBytes && n_chunks * 4 >= 4096 &&
+           n_chunks <= 0x7FFFFFFFull;
+}
+
+hipError_t launch_verify_chunks(const TileTables& t, uint64_t chunk_bytes, uint32_t tile_bytes,
+                                uint32_t plan_tiles_per_chunk, uint32_t affine, const void* chunks,
+                                const uint32_t* crcs, uint32_t* bad, uint64_t* n_bad,
+                                uint64_t n_chunks, hipStream_t stream)
+{
+    if (!verify_chunks_applicable(chunk_bytes, n_chunks)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(1), 0, stream, n_bad);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const uint8_t* c = static_cast<const uint8_t*>(chunks);
+    const bool nt = (t.hint & 2) != 0;
+    // 8 wavefronts per chunk once a share of an eighth is still 1 MiB, else 4
+    const uint32_t waves = chunk_bytes >= (8ull << 20) ? 8 : 4;
+    const uint64_t share = chunk_bytes / waves;
+    const uint32_t tiles_per_share = plan_tiles_per_chunk / waves;  // plan tiles are <= 32 KiB here
+    const uint32_t blocks_per_share = static_cast<uint32_t>(share / (kVerifyRows * kRowBytes));
+    if (tiles_per_share == 0 || uint64_t(tiles_per_share) * tile_bytes != share)
+        return hipErrorInvalidValue;
+    const dim3 grid(static_cast<unsigned>(n_chunks));
+#define FF_VLAUNCH(W, NT)                                                                         \
+    hipLaunchKernelGGL((verify_chunk_kernel<W, NT>), grid, dim3(kWaveSize* W), 0, stream, c, t.tab_u, \
+                       t.tile_shift, tiles_per_share, blocks_per_share, chunk_bytes, affine, crcs,   \
+                       bad, n_bad)
+    if (waves == 8) {
+        if (nt) FF_VLAUNCH(8, true); else FF_VLAUNCH(8, false);
+    } else {
+        if (nt) FF_VLAUNCH(4, true); else FF_VLAUNCH(4, false);
+    }
+#undef FF_VLAUNCH
     return hipGetLastError();
 }
 

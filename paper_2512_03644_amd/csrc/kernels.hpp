@@ -79,6 +79,15 @@ hipError_t launch_finish_crc(const uint32_t* partial, uint32_t n_tiles, uint32_t
                              const uint8_t* tail, uint32_t tail_bytes, uint32_t affine,
                              uint32_t* out, hipStream_t stream);
 
+// Verify pass over every chunk of a buffer with one workgroup per chunk (no atomics on the
+// per-chunk words, no preset, no finish): sets *n_bad = 0, then bad[j] and *n_bad.  Usable when
+// verify_chunks_applicable(); t supplies the tables (tile_shift for the plan's own tile size).
+bool verify_chunks_applicable(uint64_t chunk_bytes, uint64_t n_chunks);
+hipError_t launch_verify_chunks(const TileTables& t, uint64_t chunk_bytes, uint32_t tile_bytes,
+                                uint32_t plan_tiles_per_chunk, uint32_t affine, const void* chunks,
+                                const uint32_t* crcs, uint32_t* bad, uint64_t* n_bad,
+                                uint64_t n_chunks, hipStream_t stream);
+
 hipError_t launch_zero_u64(uint64_t* p, hipStream_t stream);
 
 hipError_t launch_copy(void* dst, const void* src, uint64_t nbytes, hipStream_t stream);
