@@ -321,6 +321,16 @@ int ff_crc32c_noalloc(const void *dev_buf, uint64_t nbytes, uint32_t *dev_out, v
  * bandwidth ceiling printed beside the real kernels. */
 int ff_copy_ceiling(void *dst, const void *src, uint64_t nbytes, void *hip_stream);
 
+/* Bench helper: the memory traffic of the optimizer steps with nothing else -- for every
+ * parameter group of the plan the same tiles, loads and stores as ff_adam_step_snapshot
+ * (prev_chunks NULL: 14 bytes read, 28 written per element) or as ff_adam_step_chained
+ * (prev_chunks set: 14 read, 16 written), but no arithmetic and no CRC: the new 16-bit weights are
+ * the gradient's bits, master, m and v keep their values.  crcs, RAW segments and the zero tail
+ * of `chunks` are not written.  The measured ceiling of this mix of streams, printed beside the
+ * real steps.  Arguments as for those steps. */
+int ff_mix_ceiling(const ff_plan *plan, const void *const *grads, const void *prev_chunks,
+                   void *chunks, void *hip_stream);
+
 /* Static string for a status code; for FF_ERR_HIP the text of the last HIP error seen by the
  * calling thread is appended. */
 const char *ff_strerror(int status);

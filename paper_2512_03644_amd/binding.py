@@ -43,7 +43,7 @@ EXPORTS = ["ff_snapshot_plan", "ff_plan_destroy", "ff_plan_payload_bytes", "ff_p
            "ff_plan_num_params", "ff_plan_layout_id", "ff_plan_segment_range",
            "ff_plan_chunk_span", "ff_razor_select", "ff_pack", "ff_pack_to_host", "ff_restore", "ff_restore_checked", "ff_restore_chunks", "ff_adam_step_snapshot",
            "ff_adam_step_snapshot_f16", "ff_adam_step_chained", "ff_crc32c", "ff_crc32c_noalloc",
-           "ff_copy_ceiling", "ff_strerror"]
+           "ff_copy_ceiling", "ff_mix_ceiling", "ff_strerror"]
 
 
 class ff_segment(ctypes.Structure):
@@ -123,6 +123,8 @@ def lib():
         L.ff_crc32c.restype, L.ff_crc32c.argtypes = i32, [vp, u64, vp, vp]
         L.ff_crc32c_noalloc.restype, L.ff_crc32c_noalloc.argtypes = i32, [vp, u64, vp, vp]
         L.ff_copy_ceiling.restype, L.ff_copy_ceiling.argtypes = i32, [vp, vp, u64, vp]
+        L.ff_mix_ceiling.restype = i32
+        L.ff_mix_ceiling.argtypes = [vp, ctypes.POINTER(vp), vp, vp, vp]
         L.ff_strerror.restype, L.ff_strerror.argtypes = ctypes.c_char_p, [i32]
         _lib = L
     return _lib
@@ -309,6 +311,14 @@ def ff_crc32c_noalloc(buf, nbytes, out, stream=None):
 
 def ff_copy_ceiling(dst, src, nbytes, stream=None):
     _check(lib().ff_copy_ceiling(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream)))
+
+
+def ff_mix_ceiling(plan, grads, prev_chunks, chunks, stream=None):
+    """The optimizer steps' loads and stores alone (prev_chunks None: in-place mix; else chained)."""
+    ptrs = (ctypes.c_void_p * max(len(grads), 1))(*[g.data_ptr() for g in grads])
+    _check(lib().ff_mix_ceiling(plan.handle, ptrs,
+                                prev_chunks.data_ptr() if prev_chunks is not None else None,
+                                chunks.data_ptr(), _stream_ptr(stream)))
 
 
 def alloc_outputs(plan, device):

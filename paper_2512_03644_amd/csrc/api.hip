@@ -382,11 +382,11 @@ int check_restore_args(const ff_plan* p, const void* chunks, const uint32_t* crc
 // prev: null for the in-place step; else the snapshot that holds the old master, m and v.
 int adam_impl(const ff_plan* p, const void* const* grads, const ff_adam_hparams* hp,
               uint32_t half_dtype, float inv_scale, uint64_t* n_nonfinite, const void* prev,
-              void* chunks, uint32_t* crcs, hipStream_t s)
+              void* chunks, uint32_t* crcs, hipStream_t s, bool bare = false)
 {
     int rc = check_device_call(p);
     if (rc != FF_OK) return rc;
-    if (!grads || !hp || !chunks || !crcs) return FF_ERR_NULL;
+    if (!grads || !hp || !chunks || (!crcs && !bare)) return FF_ERR_NULL;
     const Layout& L = p->layout;
     if (!L.adam_ok || L.params.empty() || hp->step == 0) return FF_ERR_INVALID;
     if (L.half_dtype != half_dtype) return FF_ERR_INVALID;  // bf16 plan <-> fp16 call or vice versa
@@ -424,7 +424,7 @@ int adam_impl(const ff_plan* p, const void* const* grads, const ff_adam_hparams*
                             p->n_work - p->n_work_param, grads,
                             static_cast<uint32_t>(L.params.size()), p->group_tile_begin.data(),
                             p->fused_tabs, chunks, crcs, L.n_chunks, L.payload, L.buffer_bytes,
-                            p->affine, c, s));
+                            p->affine, c, bare, s));
     return FF_OK;
 }
 
@@ -575,6 +575,16 @@ int ff_adam_step_chained(const ff_plan* p, const void* const* grads, const ff_ad
     if (reinterpret_cast<uint64_t>(n_nonfinite) % 8) return FF_ERR_INVALID;
     return adam_impl(p, grads, hp, half == FF_F16 ? FF_F16 : FF_BF16, inv_loss_scale, n_nonfinite,
                      prev_chunks, chunks, crcs, static_cast<hipStream_t>(hip_stream));
+}
+
+int ff_mix_ceiling(const ff_plan* p, const void* const* grads, const void* prev_chunks,
+                   void* chunks, void* hip_stream)
+{
+    if (!p) return FF_ERR_NULL;
+    const ff_adam_hparams hp = {0.f, 0.f, 0.f, 0.f, 0.f, 1u};  // unused by the bare pattern
+    const uint32_t half = p->layout.half_dtype == FF_F16 ? FF_F16 : FF_BF16;
+    return adam_impl(p, grads, &hp, half, 1.0f, nullptr, prev_chunks, chunks, nullptr,
+                     static_cast<hipStream_t>(hip_stream), true);
 }
 
 int ff_crc32c(const void* dev_buf, uint64_t nbytes, uint32_t* dev_out, void* hip_stream)

@@ -558,6 +558,184 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void fused_kernel(
     }
 }
 
+// ---- the step's traffic alone (bench helper) -------------------------------------------------------
+//
+// The loads and stores of a parameter tile with no arithmetic and no CRC, in the shape that moved
+// this mix of streams fastest in microbenchmarks: a workgroup of 4 wavefronts stages half a tile
+// (at most 4096 elements, 56 KiB) in LDS in two phases.  Load: the 1 KiB rows of the four input
+// streams -- gradient, master, m, v -- form one list that is cut into four equal runs, and every
+// wavefront requests its run up front, so a wavefront sweeps contiguous memory of one or two
+// streams.  Store: the rows of the eight output streams -- in place x 4, snapshot x 4 -- form one
+// list cut the same way.  The new 16-bit weights are the gradient's bits; master, m, v keep their
+// values.  Overlap of loads and stores comes from the two workgroups a CU holds being in different
+// phases.  (With the update and the CRC added this shape loses to fused_kernel: a tile must fit
+// LDS whole, which halves it, and the per-tile reductions and the update, done in phases of their
+// own, then take more ALU time per element than the memory phases leave.)
+// Every stream's image in LDS is aligned to its END: a stream of nbytes takes rows = ceil(nbytes /
+// 1 KiB) rows and starts pad = rows * 1 KiB - nbytes bytes into its first row.
+
+constexpr int kStageWaves = 4;
+constexpr int kStageThreads = kStageWaves * kWaveSize;
+constexpr int kStageElems = 4096;
+constexpr int kRowsF = kStageElems * 4 / 1024;  // rows of a whole fp32 stream of a half tile
+constexpr int kRowsW = kStageElems * 2 / 1024;  // rows of a whole 16-bit stream
+constexpr int kRowsIn = kRowsW + 3 * kRowsF;
+static_assert(kRowsIn % kStageWaves == 0, "whole half tiles split evenly");
+static_assert(kParamTileElems <= 2 * kStageElems, "a parameter tile is staged in two halves");
+
+struct StageGeom {
+    int n;               // elements
+    int rows_w, rows_f;  // rows of the 16-bit stream / of each fp32 stream
+    int pad_w, pad_f;    // bytes in front of the data in row 0
+};
+
+// byte offset of stream x's image (0: w16 / gradient, 1..3: master, m, v) in LDS
+__device__ __forceinline__ int stage_base(int x)
+{
+    return x == 0 ? 0 : kRowsW * 1024 + (x - 1) * kRowsF * 1024;
+}
+
+template <bool CHAINED>
+__global__ __launch_bounds__(kStageThreads) void mix_ceiling_kernel(
+    const WorkTile* __restrict__ tiles, uint32_t n_tiles, uint32_t grad_base,
+    uint8_t* __restrict__ chunks, FusedConsts C, GradPtrs grads)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t img[kRowsIn * 1024];
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
+    // workgroup position p: half p mod 2 of tile p div 2
+    const uint32_t pos = xcd_order(blockIdx.x, gridDim.x, C.xcd_group);
+    const uint32_t ti = pos / 2;
+    if (ti >= n_tiles) return;
+    const WorkTile& t = tiles[ti];
+    if (t.kind != kWorkParam) return;
+    const int e_off = static_cast<int>(pos % 2) * kStageElems;  // first element of this half
+    if (e_off >= static_cast<int>(t.n)) return;
+    StageGeom G;
+    G.n = static_cast<int>(t.n) - e_off < kStageElems ? static_cast<int>(t.n) - e_off : kStageElems;
+    G.rows_w = (2 * G.n + 1023) / 1024;
+    G.rows_f = (4 * G.n + 1023) / 1024;
+    G.pad_w = G.rows_w * 1024 - 2 * G.n;
+    G.pad_f = G.rows_f * 1024 - 4 * G.n;
+    const uint32_t lane16 = 16u * lane;
+    auto elem_bytes = [](int x) { return x == 0 ? 2 : 4; };
+
+    // ---- load ------------------------------------------------------------------------------------
+    {
+        // where stream x is read from: the gradient; master, m, v from their tensors or, chained,
+        // from the previous snapshot at their stream offsets
+        const uint8_t* src[4];
+        src[0] = reinterpret_cast<const uint8_t*>(grads.p[t.grad_index - grad_base]) +
+                 2 * (t.e0 + e_off);
+#pragma unroll
+        for (int x = 1; x < 4; x++)
+            src[x] = (CHAINED ? C.prev + t.soff[x] : reinterpret_cast<const uint8_t*>(t.ptr[x])) +
+                     4 * e_off;
+        const int total = G.rows_w + 3 * G.rows_f;
+        const int per = (total + kStageWaves - 1) / kStageWaves;
+        constexpr int kPer = kRowsIn / kStageWaves;
+        u32x4 q[kPer];
+        // row i of this wavefront's run: which stream, which row of it (x < 0: none)
+        auto decode = [&](int i, int& x, int& r) {
+            const int rr = wave * per + i;
+            x = -1;
+            r = rr;
+            if (i < per && rr < total) {
+                x = 0;
+                if (r >= G.rows_w) {
+                    r -= G.rows_w;
+                    x = 1;
+                    if (r >= G.rows_f) { r -= G.rows_f; x = 2; }
+                    if (r >= G.rows_f) { r -= G.rows_f; x = 3; }
+                }
+            }
+        };
+        static_for<kPer>([&](auto ic) {
+            constexpr int i = ic;
+            int x, r;
+            decode(i, x, r);
+            q[i] = u32x4{0, 0, 0, 0};
+            if (x >= 0) {
+                const uint8_t* sp = x == 0 ? src[0] : (x == 1 ? src[1] : (x == 2 ? src[2] : src[3]));
+                const int pad = x == 0 ? G.pad_w : G.pad_f;
+                const int off = r * 1024 + static_cast<int>(lane16) - pad;  // in the stream's data
+                if (off >= 0) {
+                    q[i] = load16_unaligned<true>(sp + off);
+                } else if (off > -16) {
+                    // the lane's 16 bytes begin in the pad (row 0 only): halfword by halfword
+                    uint32_t h[8];
+#pragma unroll
+                    for (int u = 0; u < 8; u++) {
+                        const int b = off + 2 * u;
+                        h[u] = b >= 0 ? *as_global(reinterpret_cast<const uint16_t*>(sp + b)) : 0u;
+                    }
+                    q[i] = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16),
+                                 h[6] | (h[7] << 16)};
+                }
+            }
+        });
+        static_for<kPer>([&](auto ic) {
+            constexpr int i = ic;
+            int x, r;
+            decode(i, x, r);
+            if (x >= 0) *reinterpret_cast<u32x4*>(&img[stage_base(x) + r * 1024 + lane16]) = q[i];
+        });
+    }
+    __syncthreads();
+
+    // ---- store -----------------------------------------------------------------------------------
+    {
+        // The output streams in the order their rows are listed: in place master, m, v (not when
+        // chained), in place w16, then snapshot master, m, v, w16.  o counts through that list;
+        // stream_of(o) is the image it is taken from.
+        constexpr int kOut = CHAINED ? 5 : 8;
+        constexpr int kInPlace = CHAINED ? 1 : 4;
+        auto stream_of = [&](int o) {
+            return o < kInPlace ? (o == kInPlace - 1 ? 0 : o + 1) : ((o - kInPlace + 1) & 3);
+        };
+        auto rows_of = [&](int o) { return stream_of(o) == 0 ? G.rows_w : G.rows_f; };
+        const int total = (kOut - 2) * G.rows_f + 2 * G.rows_w;
+        const int per = (total + kStageWaves - 1) / kStageWaves;
+        constexpr int kPer = 2 * kRowsIn / kStageWaves;
+        // this wavefront's run starts at row r of output stream o
+        int o = 0, r = wave * per;
+        static_for<kOut>([&](auto) {
+            if (o < kOut && r >= rows_of(o)) {
+                r -= rows_of(o);
+                o++;
+            }
+        });
+        static_for<kPer>([&](auto ic) {
+            constexpr int i = ic;
+            if (i < per && o < kOut) {
+                const int x = stream_of(o);
+                const int pad = x == 0 ? G.pad_w : G.pad_f;
+                uint8_t* const d = (o < kInPlace ? reinterpret_cast<uint8_t*>(t.ptr[x]) : chunks + t.soff[x]) +
+                                   elem_bytes(x) * e_off;
+                const u32x4 w = *reinterpret_cast<const u32x4*>(&img[stage_base(x) + r * 1024 + lane16]);
+                const int off = r * 1024 + static_cast<int>(lane16) - pad;
+                if (off >= 0) {
+                    store16_unaligned<true>(d + off, w);
+                } else if (off > -16) {
+                    const uint32_t dd[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                    for (int u = 0; u < 8; u++) {
+                        const int b = off + 2 * u;
+                        if (b >= 0)
+                            *as_global(reinterpret_cast<uint16_t*>(d + b)) =
+                                static_cast<uint16_t>(dd[u >> 1] >> ((u & 1) * 16));
+                    }
+                }
+                r++;
+                if (r >= rows_of(o)) {
+                    r = 0;
+                    o++;
+                }
+            }
+        });
+    }
+}
+
 // RAW tiles: one wavefront per tile copies its bytes into the snapshot and folds them.
 constexpr int kRawWaves = 4;
 __global__ __launch_bounds__(kWaveSize* kRawWaves) void raw_kernel(
@@ -611,20 +789,26 @@ hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_param_tiles,
                         uint32_t n_raw_tiles, const void* const* grads, uint32_t n_params,
                         const uint32_t* group_tile_begin, const uint32_t* tabs, void* chunks,
                         uint32_t* crcs, uint64_t n_chunks, uint64_t payload, uint64_t buffer_bytes,
-                        uint32_t affine, const FusedConsts& consts, hipStream_t stream)
+                        uint32_t affine, const FusedConsts& consts, bool bare, hipStream_t stream)
 {
     uint8_t* c = static_cast<uint8_t*>(chunks);
-    const uint64_t prep_items = n_chunks > (buffer_bytes - payload) / 2 ? n_chunks
-                                                                         : (buffer_bytes - payload) / 2;
-    unsigned prep_blocks = static_cast<unsigned>((prep_items + 255) / 256);
-    if (prep_blocks == 0) prep_blocks = 1;
-    if (prep_blocks > 4096) prep_blocks = 4096;
-    hipLaunchKernelGGL(fused_prepare_kernel, dim3(prep_blocks), dim3(256), 0, stream, crcs, n_chunks,
-                       affine, c, payload, buffer_bytes, f16 ? consts.n_nonfinite : nullptr);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    auto kernel = consts.prev ? (f16 ? fused_kernel<true, true> : fused_kernel<false, true>)
-                              : (f16 ? fused_kernel<true, false> : fused_kernel<false, false>);
+    hipError_t e = hipSuccess;
+    if (!bare) {
+        const uint64_t prep_items = n_chunks > (buffer_bytes - payload) / 2
+                                        ? n_chunks
+                                        : (buffer_bytes - payload) / 2;
+        unsigned prep_blocks = static_cast<unsigned>((prep_items + 255) / 256);
+        if (prep_blocks == 0) prep_blocks = 1;
+        if (prep_blocks > 4096) prep_blocks = 4096;
+        hipLaunchKernelGGL(fused_prepare_kernel, dim3(prep_blocks), dim3(256), 0, stream, crcs,
+                           n_chunks, affine, c, payload, buffer_bytes,
+                           f16 ? consts.n_nonfinite : nullptr);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    const bool chained = consts.prev != nullptr;
+    auto kernel = chained ? (f16 ? fused_kernel<true, true> : fused_kernel<false, true>)
+                          : (f16 ? fused_kernel<true, false> : fused_kernel<false, false>);
     // one launch per kGradsPerLaunch parameter groups; the parameter tiles are sorted by group
     for (uint32_t k = 0, p0 = 0; p0 < n_params && n_param_tiles; k++, p0 += kGradsPerLaunch) {
         const uint32_t t0 = group_tile_begin[k], t1 = group_tile_begin[k + 1];
@@ -632,12 +816,23 @@ hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_param_tiles,
         GradPtrs g;
         for (uint32_t i = 0; i < kGradsPerLaunch; i++)
             g.p[i] = p0 + i < n_params ? reinterpret_cast<uint64_t>(grads[p0 + i]) : 0;
-        hipLaunchKernelGGL(kernel, dim3(t1 - t0), dim3(kWaveSize * kWavesPerBlock), 0, stream,
-                           tiles + t0, t1 - t0, p0, tabs, c, crcs, consts, g);
+        if (bare) {
+            // two workgroups per tile, one per half
+            if (chained)
+                hipLaunchKernelGGL(mix_ceiling_kernel<true>, dim3(2 * (t1 - t0)), dim3(kStageThreads),
+                                   0, stream, tiles + t0, t1 - t0, p0, c, consts, g);
+            else
+                hipLaunchKernelGGL(mix_ceiling_kernel<false>, dim3(2 * (t1 - t0)),
+                                   dim3(kStageThreads), 0, stream, tiles + t0, t1 - t0, p0, c, consts,
+                                   g);
+        } else {
+            hipLaunchKernelGGL(kernel, dim3(t1 - t0), dim3(kWaveSize * kWavesPerBlock), 0, stream,
+                               tiles + t0, t1 - t0, p0, tabs, c, crcs, consts, g);
+        }
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    if (n_raw_tiles) {
+    if (n_raw_tiles && !bare) {
         const unsigned grid = (n_raw_tiles + kRawWaves - 1) / kRawWaves;
         hipLaunchKernelGGL(raw_kernel, dim3(grid), dim3(kWaveSize * kRawWaves), 0, stream,
                            tiles + n_param_tiles, n_raw_tiles, tabs, c, crcs);

@@ -41,11 +41,14 @@ struct GradPtrs {
 // the parameter tiles first, sorted by parameter group, then the RAW tiles (a kernel of their own).
 // grads: HOST array of n_params device pointers, read during the call only.  group_tile_begin:
 // HOST array, entry k = index of the first parameter tile of group k * kGradsPerLaunch, one more
-// entry = n_param_tiles.  f16: gradients and working weights are fp16 (else bf16).
+// entry = n_param_tiles.  f16: gradients and working weights are fp16 (else bf16).  bare: the
+// step's traffic alone -- every parameter tile's loads and stores with no arithmetic and no CRC
+// (16-bit weights := gradient bits, master, m, v unchanged); crcs, the RAW segments and the zero
+// tail are not touched.
 hipError_t launch_fused(bool f16, const WorkTile* tiles, uint32_t n_param_tiles,
                         uint32_t n_raw_tiles, const void* const* grads, uint32_t n_params,
                         const uint32_t* group_tile_begin, const uint32_t* tabs, void* chunks,
                         uint32_t* crcs, uint64_t n_chunks, uint64_t payload, uint64_t buffer_bytes,
-                        uint32_t affine, const FusedConsts& consts, hipStream_t stream);
+                        uint32_t affine, const FusedConsts& consts, bool bare, hipStream_t stream);
 
 }  // namespace ffsnap

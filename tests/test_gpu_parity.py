@@ -316,6 +316,62 @@ def test_copy_ceiling_copies_exactly(nbytes):
     assert bool((dst[:64] == 0xA5).all()) and bool((dst[64 + nbytes:] == 0xA5).all())
 
 
+@pytest.mark.parametrize("chunk,chained", [(1024, False), (1 << 16, False), (1 << 20, True), (4096, True)])
+def test_mix_ceiling_moves_exactly_the_steps_bytes(chunk, chained):
+    """The bench's ceiling for the optimizer steps' traffic: same tiles, loads and stores, no
+    arithmetic, no CRC.  It is checked byte for byte: snapshot ranges of every group hold the
+    gradient's bits (as the new 16-bit weights) and master, m, v unchanged; the tensors likewise;
+    RAW ranges and the zero tail of the buffer are not touched."""
+    numels = [1, 3, 255, 256, 257, 1000, 4095, 4096, 4097, 8191, 8192, 8193, 70001, 12289, 5, 77]
+    shard = wl.param_shard("mix", numels, chunk, 9, DEV, with_grads=True)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(2)
+    raw = torch.randn(3001, device=DEV, generator=g)
+    tensors = list(shard.segments)
+    kinds, pids = [], []
+    for pid in range(len(shard.params)):
+        kinds += [ff.FF_KIND_W16, ff.FF_KIND_MASTER, ff.FF_KIND_M, ff.FF_KIND_V]
+        pids += [pid] * 4
+    tensors.insert(8, raw)
+    kinds.insert(8, ff.FF_KIND_RAW)
+    pids.insert(8, 0)
+    plan = ff.ff_snapshot_plan(tensors, chunk, kinds=kinds, param_ids=pids)
+    chunks, crcs, _, _ = ff.alloc_outputs(plan, DEV)
+    grads = [p.grad for p in shard.params]
+    before = [t.clone() for t in tensors]
+    prev = None
+    if chained:
+        prev, prev_crcs, _, _ = ff.alloc_outputs(plan, DEV)
+        ff.ff_pack(plan, prev, prev_crcs)          # the state the chained pattern reads
+        for p in shard.params:
+            for t in (p.master, p.m, p.v):
+                t.view(torch.int32).fill_(0x7FC00BAD)
+    chunks.fill_(0xA5)
+    crcs.fill_(0x5A5A5A5A)
+    ff.ff_mix_ceiling(plan, grads, prev, chunks)
+    torch.cuda.synchronize()
+    assert bool((crcs == 0x5A5A5A5A).all())
+    got = chunks.cpu().numpy()
+    covered = np.zeros(got.size, dtype=bool)
+    for i, (t, b4) in enumerate(zip(tensors, before)):
+        lo, hi = plan.segment_range(i)
+        if kinds[i] == ff.FF_KIND_RAW:
+            assert torch.equal(t, b4)
+            continue
+        covered[lo:hi] = True
+        if kinds[i] == ff.FF_KIND_W16:
+            want = wl.to_numpy_bytes(grads[pids[i]])
+            assert np.array_equal(wl.to_numpy_bytes(t), want), i        # in place: gradient bits
+        else:
+            want = wl.to_numpy_bytes(b4)
+            if chained:   # master, m, v tensors are neither read nor written
+                assert bool((t.view(torch.int32) == 0x7FC00BAD).all()), i
+            else:
+                assert np.array_equal(wl.to_numpy_bytes(t), want), i
+        assert np.array_equal(got[lo:hi], want), i
+    assert bool((got[~covered] == 0xA5).all())
+
+
 def test_one_plan_on_two_streams_at_once(oracle):
     """A plan is immutable: calls on ONE plan may overlap in time as long as their outputs differ.
     Two streams pack the same shard into two buffers and verify them concurrently, several times
