@@ -40,17 +40,24 @@ def kernel_source_hash():
     return h.hexdigest()
 
 
-def measured_traffic(kernel):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter runs
-    (profiles/hbm_traffic.json), or None if the sources have changed since they were taken."""
+def measured_traffic(kernel, workload):
+    """(HBM bytes per launch of `kernel` on `workload`, where the figure comes from) out of the
+    committed rocprofv3 counter runs (profiles/hbm_traffic.json); (None, reason) if the kernel
+    sources have changed since the counters were taken or the kernel was not counted."""
     try:
         rec = json.load(open(os.path.join(ROOT, "profiles", "hbm_traffic.json")))
     except (OSError, ValueError):
-        return None
+        return None, "no counter record"
     if rec.get("source_sha256") != kernel_source_hash():
-        return None
-    k = rec.get("kernels", {}).get(kernel)
-    return None if k is None else k["hbm_bytes_per_launch"]
+        return None, "kernel sources changed since the counters in profiles/hbm_traffic.json were taken"
+    k = rec.get("workloads", {}).get(workload, {}).get(kernel)
+    if k is None:
+        return None, "kernel not in profiles/hbm_traffic.json for this workload"
+    return k["hbm_bytes_per_launch"], (
+        "replayed, not measured in this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+        "command committed in profiles/hbm_traffic.json (same kernel sources by hash), scaled by "
+        "the same counters on the library's plain copy kernel; cross-checked there against "
+        "TCC_EA0_RDREQ / TCC_EA0_WRREQ")
 
 
 def parse():
@@ -60,6 +67,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-adam", action="store_true", help="leave the fused optimizer step out")
+    ap.add_argument("--no-host-staging", action="store_true",
+                    help="leave out the snapshot-to-pinned-host-memory timing (it pins a buffer "
+                         "as large as the snapshot)")
     ap.add_argument("--tile-log2", type=int, default=0, help="tuning: log2 of the tile size")
     ap.add_argument("--workload", default="llama7b",
                     choices=["llama7b", "llama70b", "fragmented", "tiny"],
@@ -120,14 +130,16 @@ def cpu_baseline(shard, n_params, hp, with_adam, torch):
     """The oracle's step on a bounded sample of the shard: on all host cores available to the
     process (chunk ranges and parameters spread by a thread pool) and, on a smaller sample, on
     one core."""
-    cores = min(16, len(os.sched_getaffinity(0)))
+    # the box gives one GPU's job 16 cores' worth of CPU time whatever the affinity mask shows
+    available = len(os.sched_getaffinity(0))
+    cores = min(16, available)
     step_bytes, nbytes, t = cpu_oracle_step(shard, n_params, hp, with_adam, cores)
     n_one = max(1, min(n_params, 6))
     one_bytes, one_payload, t_one = cpu_oracle_step(shard, n_one, hp, with_adam, 1)
     what = "oracle %spack, restore; bytes counted as for the GPU step" % (
         "AdamW update + pack (unfused), " if with_adam else "")
     return {"value": round(step_bytes / sum(t) / 1e9, 3), "unit": "GB/s", "cores": cores,
-            "kind": "oracle",
+            "cores_in_affinity_mask": available, "kind": "oracle",
             "sample": "first %d of %d parameter groups of the same shard (%.2f GB payload): %s; "
                       "wall %.2f + %.2f + %.2f s" % ((n_params, len(shard.params), nbytes / 1e9,
                                                       what) + t),
@@ -136,6 +148,64 @@ def cpu_baseline(shard, n_params, hp, with_adam, torch):
                               "sample": "first %d parameter groups (%.2f GB payload), same steps; "
                                         "wall %.2f + %.2f + %.2f s"
                                         % ((n_one, one_payload / 1e9) + t_one)}}
+
+
+def selective_restore(ff, wl, torch, plan, chunks, crcs, bad, n_bad, N):
+    """Failover-side variants, timed on the packed buffer with 1 % of its chunks corrupted (one
+    flipped bit each, the seeded recipe of the corruption configuration): restore that leaves the
+    ranges of bad chunks alone, and restore of just those chunks once they have been fetched
+    again.  The buffer is repaired afterwards."""
+    C = plan.chunk_bytes
+    ff.ff_pack(plan, chunks, crcs)     # the copy-ceiling run overwrote the buffer
+    hits = wl.corrupt_chunks(plan.num_chunks, C)
+    for c, off, bit in hits:
+        chunks[c * C + off] ^= (1 << bit)
+    ts = event_ms(lambda: ff.ff_restore(plan, chunks, crcs, bad, n_bad,
+                                        flags=ff.FF_RESTORE_SKIP_BAD), 5, torch)
+    found = int(n_bad.item())
+    for c, off, bit in hits:
+        chunks[c * C + off] ^= (1 << bit)
+    ids = [c for c, _, _ in hits]
+    ts2 = event_ms(lambda: ff.ff_restore_chunks(plan, chunks, crcs, ids, bad, n_bad), 5, torch)
+    assert found == len(hits) and int(n_bad.item()) == 0
+    skip_ms, sel_ms = sum(ts) / len(ts), sum(ts2) / len(ts2)
+    return {"restore_skip_bad": {"avg_ms": round(skip_ms, 4), "bad_chunks": found,
+                                 "bytes": 3 * N, "traffic_GBps": round(3 * N / skip_ms / 1e6, 1)},
+            "restore_chunks": {"avg_ms": round(sel_ms, 4), "chunks": len(ids),
+                               "payload_GBps": round(len(ids) * C / sel_ms / 1e6, 1)}}
+
+
+def pack_to_host(ff, torch, plan, chunks, crcs, N):
+    """Snapshot into pinned host memory (the paper's device-to-host step): pack, then copy, against
+    pack overlapped with the copy slice by slice.  Crosses PCIe: reported beside the step, never
+    part of `value`."""
+    h_chunks = torch.empty(plan.buffer_bytes, dtype=torch.uint8, pin_memory=True)
+    h_crcs = torch.empty(plan.num_chunks, dtype=torch.int32, pin_memory=True)
+    s_pack, s_copy = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def serial():
+        ff.ff_pack(plan, chunks, crcs)
+        h_chunks.copy_(chunks, non_blocking=True)
+        h_crcs.copy_(crcs, non_blocking=True)
+
+    def overlapped():
+        s_pack.wait_stream(torch.cuda.current_stream())
+        ff.ff_pack_to_host(plan, chunks, crcs, h_chunks, h_crcs, 64, s_pack, s_copy)
+        torch.cuda.current_stream().wait_stream(s_copy)
+
+    out = {}
+    for name, fn in (("pack_then_copy", serial), ("overlapped", overlapped)):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / 2 * 1e3
+        out[name] = {"ms": round(ms, 2), "payload_GBps": round(N / ms / 1e6, 1)}
+    out["slice_chunks"] = 64
+    del h_chunks, h_crcs
+    return out
 
 
 def main():
@@ -234,15 +304,21 @@ def main():
     for name in detail:
         detail[name]["frac_of_copy_ceiling"] = round(detail[name]["traffic_GBps"] / copy_gbs, 4)
 
+    # the quantity the metric names: pack+CRC and restore together
+    pr_ms = detail["pack"]["avg_ms"] + detail["restore"]["avg_ms"]
+    pack_restore = {"ms": round(pr_ms, 4), "bytes": 4 * N, "GBps": round(4 * N / pr_ms / 1e6, 1),
+                    "frac_of_peak": round(4 * N / pr_ms / 1e6 / HBM_PEAK_GBS, 4)}
+
     # roofline of the dominant (longest-running) kernel of the step
     kernels = {"adam_snapshot": ("fused_kernel", 42 * n_el), "pack": ("tile_kernel<pack>", 2 * N),
                "restore": ("tile_kernel<restore>", 2 * N)}
     dom = max(detail, key=lambda k: detail[k]["avg_ms"])
     kname, kbytes = kernels[dom]
     achieved = kbytes / detail[dom]["avg_ms"] / 1e6
+    traffic, traffic_source = measured_traffic(kname, args.workload)
     roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic(kname) if args.workload == "llama7b" else None,
+                "traffic": traffic, "traffic_source": traffic_source,
                 "algorithmic_bytes_per_launch": kbytes,
                 "avg_launch_ms": detail[dom]["avg_ms"],
                 "copy_ceiling_GBps": round(copy_gbs, 1)}
@@ -254,6 +330,21 @@ def main():
     extra = {"verify_only": {"avg_ms": round(verify_ms, 4),
                              "payload_GBps": round(N / verify_ms / 1e6, 1),
                              "frac_of_peak": round(N / verify_ms / 1e6 / HBM_PEAK_GBS, 4)}}
+    extra.update(selective_restore(ff, wl, torch, plan, chunks, crcs, bad, n_bad, N))
+    if not args.no_host_staging:
+        extra["pack_to_host"] = pack_to_host(ff, torch, plan, chunks, crcs, N)
+    if with_adam:
+        # the traffic of the optimizer step alone, in the fastest shape found for this mix of
+        # streams (no arithmetic, no CRC): the measured ceiling beside the fused kernel
+        ff.ff_pack(plan, chunks, crcs)
+        ts = event_ms(lambda: ff.ff_mix_ceiling(plan, grads, None, chunks), 5, torch)
+        mix_ms = sum(ts) / len(ts)
+        extra["mix_ceiling"] = {"avg_ms": round(mix_ms, 4), "bytes_per_launch": 42 * n_el,
+                                "traffic_GBps": round(42 * n_el / mix_ms / 1e6, 1),
+                                "frac_of_peak": round(42 * n_el / mix_ms / 1e6 / HBM_PEAK_GBS, 4)}
+        detail["adam_snapshot"]["frac_of_mix_ceiling"] = round(
+            mix_ms / detail["adam_snapshot"]["avg_ms"], 4)
+        roofline["mix_ceiling_GBps"] = extra["mix_ceiling"]["traffic_GBps"]
     if with_adam:
         # The fused step with the optimizer state kept in the two alternating snapshots (reads
         # 14 B and writes 16 B per element): reported beside the step, not part of it.  It runs
@@ -271,10 +362,14 @@ def main():
         ff.ff_restore(plan, pair[0][0], pair[0][1], bad, n_bad, flags=ff.FF_RESTORE_VERIFY_ONLY)
         torch.cuda.synchronize()
         assert int(n_bad.item()) == 0
+        ts2 = event_ms(lambda: ff.ff_mix_ceiling(plan, grads, pair[0][0], pair[1][0]), 5, torch)
+        mixc_ms = sum(ts2) / len(ts2)
         extra["adam_chained"] = {"avg_ms": round(chained_ms, 4), "min_ms": round(min(ts), 4),
                                  "bytes_per_launch": 30 * n_el,
                                  "traffic_GBps": round(30 * n_el / chained_ms / 1e6, 1),
-                                 "frac_of_peak": round(30 * n_el / chained_ms / 1e6 / HBM_PEAK_GBS, 4)}
+                                 "frac_of_peak": round(30 * n_el / chained_ms / 1e6 / HBM_PEAK_GBS, 4),
+                                 "mix_ceiling_ms": round(mixc_ms, 4),
+                                 "frac_of_mix_ceiling": round(mixc_ms / chained_ms, 4)}
         del chunks2
     metric = "snapshot pack+CRC and restore GB/s, % of HBM peak, 7B-shaped shard"
     if args.workload != "llama7b":
@@ -291,7 +386,7 @@ def main():
                       "step": " + ".join(n for n, _, _ in ops),
                       "bytes_per_step": step_bytes},
            "pct_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS * 100, 2),
-           "ops": detail, "extra": extra, "roofline": roofline}
+           "pack_restore": pack_restore, "ops": detail, "extra": extra, "roofline": roofline}
     if not args.no_cpu_baseline and n_cpu_groups:
         out["cpu_baseline"] = cpu_baseline(shard, n_cpu_groups, hp, with_adam, torch)
     print(json.dumps(out))

@@ -748,7 +748,7 @@ __global__ __launch_bounds__(kWaveSize* kRawWaves) void raw_kernel(
     __syncthreads();
     const int lane = threadIdx.x & (kWaveSize - 1);
     // consecutive tiles per XCD, as in the tile kernel (a RAW tile is a 32 KiB copy as well)
-    const uint32_t ti = xcd_order(blockIdx.x, gridDim.x, 8) * kRawWaves +
+    const uint32_t ti = xcd_order(blockIdx.x, gridDim.x, kDefaultXcdGroup) * kRawWaves +
                         __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
     if (ti >= n_tiles) return;
     const WorkTile& t = tiles[ti];

@@ -714,7 +714,7 @@ __global__ __launch_bounds__(kWaveSize * kWavesPerBlock) void copy_kernel(
 {
     const uint32_t lane = threadIdx.x & (kWaveSize - 1);
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
-    const uint64_t tile = uint64_t(xcd_order(blockIdx.x, gridDim.x, 8)) * kWavesPerBlock + wave;
+    const uint64_t tile = uint64_t(xcd_order(blockIdx.x, gridDim.x, kDefaultXcdGroup)) * kWavesPerBlock + wave;
     const uint64_t i0 = tile * (kCopyRows * kWaveSize);
     if (i0 >= n16) return;
     if (i0 + kCopyRows * kWaveSize <= n16) {

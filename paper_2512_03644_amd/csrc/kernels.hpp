@@ -8,6 +8,10 @@
 
 namespace ffsnap {
 
+// Run length of the XCD-aware workgroup order (xcd_order.h) of the kernels that move 32 KiB per
+// wavefront, 128 KiB per workgroup.
+constexpr uint32_t kDefaultXcdGroup = 2048;
+
 // Device-side view of a plan's tables, plus the constants the tile kernels need.
 struct TileTables {
     const uint64_t* seg_off = nullptr;        // [n_seg + 1] stream offsets, seg_off[n_seg] = payload
@@ -44,7 +48,8 @@ struct TileTables {
     // Workgroups are dealt to the 8 XCDs round-robin.  With xcd_group = G > 0 the workgroups of
     // one XCD take G consecutive groups of tiles, the next XCD the following G, and so on, so
     // that every XCD (and its L2) sweeps runs of G * 128 KiB instead of every eighth 128 KiB.
-    uint32_t xcd_group = 8;  // measured best of 0, 8 .. 8192 (restore +5 %, pack +2 %)
+    uint32_t xcd_group = kDefaultXcdGroup;  // measured: 8 .. 2048 within 0.5 % on a 12 GB shard, 2048 best
+                                // (by 1-2 %) on a 15 GB one; 0 (launch order) costs 5-7 %
 };
 
 enum TileMode { kPack = 0, kRestore = 1, kVerify = 2 };

@@ -1,5 +1,7 @@
 // xcd_order(b, n, g) must be a permutation of [0, n) for every launch size and run length, and the
 // workgroups that one XCD receives (b mod 8 equal, consecutive in b) must take consecutive positions.
+// Behind the last complete round the run length halves until it fits: also checked, through the
+// largest run that fits a launch shorter than one round.
 #include "xcd_order.h"
 #include <cstdio>
 #include <vector>
@@ -28,6 +30,17 @@ int main()
             // every round maps onto itself
             for (uint32_t b = 0; b < full; b++)
                 if (xcd_order(b, n, g) / span != b / span) { std::printf("round left: g=%u n=%u b=%u\n", g, n, b); return 1; }
+        }
+    }
+    // a launch shorter than one round of the requested run length still gets runs: the longest
+    // power of two that fits, from workgroup 0 on
+    for (uint32_t n = 8; n <= 3000; n += 37) {
+        const uint32_t g = 1u << 11;
+        uint32_t fit = g;
+        while (8 * fit > n) fit >>= 1;
+        for (uint32_t b = 0; b + 8 < 8 * fit; b++) {
+            if ((b % (8 * fit)) + 8 >= 8 * fit) continue;
+            if (xcd_order(b + 8, n, g) != xcd_order(b, n, g) + 1) { std::printf("short launch: n=%u b=%u\n", n, b); return 1; }
         }
     }
     // a large launch, spot-checked through its inverse
