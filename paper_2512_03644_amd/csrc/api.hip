@@ -45,6 +45,7 @@ struct ff_plan {
     uint32_t n_work = 0;        // all work tiles: parameter tiles first, then RAW tiles
     uint32_t n_work_param = 0;
     uint32_t fused_xcd_group = 4;  // XCD-aware order of the fused step's tiles (kernels.hpp)
+    uint32_t mix_xcd_group = 16;   // ... and of the bare traffic pattern (its own best)
     // entry k: first parameter tile of parameter group k * kGradsPerLaunch; last entry: n_work_param
     std::vector<uint32_t> group_tile_begin;
     const uint32_t* fused_tabs = nullptr;
@@ -224,8 +225,8 @@ int ff_snapshot_plan(const ff_segment* segs, uint64_t n_segs, uint64_t chunk_byt
             delete p;
             return FF_ERR_INVALID;
         }
-        if (xg == 31u) t.xcd_group = p->fused_xcd_group = 0;
-        else if (xg) t.xcd_group = p->fused_xcd_group = 1u << (xg - 1);
+        if (xg == 31u) t.xcd_group = p->fused_xcd_group = p->mix_xcd_group = 0;
+        else if (xg) t.xcd_group = p->fused_xcd_group = p->mix_xcd_group = 1u << (xg - 1);
     }
     if (L.n_tiles > 0xFFFFFFF0ull) {
         delete p;
@@ -417,7 +418,7 @@ int adam_impl(const ff_plan* p, const void* const* grads, const ff_adam_hparams*
         c.adam.eps = hp->eps;
     }
     c.inv_scale = inv_scale;
-    c.xcd_group = p->fused_xcd_group;
+    c.xcd_group = bare ? p->mix_xcd_group : p->fused_xcd_group;
     c.n_nonfinite = n_nonfinite;
     c.prev = static_cast<const uint8_t*>(prev);
     FF_HIP_TRY(launch_fused(half_dtype == FF_F16, p->work, p->n_work_param,

@@ -150,7 +150,6 @@ def search(S, F, NE, ntaps):
 
 SETS = [
     # name, row bytes, dwords per lane, NE, taps
-    ("Fold16x24", 1024, 4, 24, 7),
     ("Fold16x16", 1024, 4, 16, 9),
     # 0 = fewest terms found by exhaustive walk of the solution set (few candidates, small state)
     ("Fold16x10", 1024, 4, 10, 0),
