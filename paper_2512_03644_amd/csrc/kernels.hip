@@ -34,17 +34,24 @@ using Fold = Fold16x16;
 constexpr int kRowBytes = Fold::ROW_BYTES;
 constexpr int kNE = Fold::NE;
 constexpr int kNF = Fold::NF;
-constexpr int kDepth = 8;  // rows in flight per wavefront
+// rows in flight per wavefront on the general path (restore keeps fewer: its general path is the
+// point of highest register pressure of the kernel, and four more rows there would push the whole
+// kernel past the 256 registers that two wavefronts per SIMD allow)
+template <int MODE>
+constexpr int kDepthOf = (MODE == kRestore) ? 4 : 8;
 // A default-size tile that lies inside one segment is processed by straight-line code with a
 // deeper queue: with no loop there is no loop-carried register to copy and no wait for all
 // outstanding loads at a loop head.
 constexpr int kWholeRows = 32;   // rows of a default (32 KiB) tile
+constexpr int kRealignDepth = 16;  // rows in flight on the restore path that re-aligns its stores
+constexpr int kRingWords = 520;  // two rows and 16 bytes, as dwords, padded to a multiple of 16 bytes
 constexpr int kVerifyRows = 64;  // a read-only pass walks its grouped tile in blocks of 64 rows
 // rows requested before the first store on that path (measured: 16 is best when the stores go to
 // the chunk buffer, the whole tile when they go to the tensors)
 template <int MODE>
 constexpr int kWholeDepth = (MODE == kRestore) ? 32 : 16;
-static_assert(kNE % kDepth == 0, "queue slots must repeat with the state rotation");
+static_assert(kNE % kDepthOf<kPack> == 0 && kNE % kDepthOf<kRestore> == 0,
+              "queue slots must repeat with the state rotation");
 static_assert(kNF == 4 && kRowBytes == 1024, "one 16-byte word per lane per row");
 
 // ---- segment cursor (wave-uniform) -----------------------------------------------------------
@@ -170,7 +177,9 @@ __device__ __forceinline__ void fold_word(uint32_t (&S)[kNE][kNF], u32x4 w)
 // ---- tile kernel -------------------------------------------------------------------------------
 
 // Three bodies, fastest first.  (1) A default-size tile that lies inside one segment (and a
-// read-only tile of the grouped size) is one piece of straight-line code over all its rows.
+// read-only tile of the grouped size) is one piece of straight-line code over all its rows; on
+// restore, such a tile whose place in the tensor is off the 128-byte lines takes a variant that
+// lines its stores up through LDS.
 // (2) A default-size tile that touches up to four segments or the end of the payload is
 // straight-line too, every lane choosing its segment by comparisons.  (3) Everything else -- other
 // tile sizes, many small segments, tiles behind the payload -- walks its rows in groups of kNE (one
@@ -183,7 +192,7 @@ __device__ __forceinline__ void tile_body(
     const uint64_t* __restrict__ seg_off, const uint64_t* __restrict__ seg_ptr,
     const uint32_t* __restrict__ tile_first_seg, const uint32_t* __restrict__ tab_u_global,
     uint32_t* __restrict__ partial, uint32_t* __restrict__ acc, uint8_t* __restrict__ chunks,
-    const TileTables& T, const uint32_t* tab, const uint32_t tile, const int lane)
+    const TileTables& T, const uint32_t* tab, uint32_t* ring, const uint32_t tile, const int lane)
 {
     // constant that moves this tile's register to the end of its chunk (tiles per chunk is a
     // power of two) and supplies the factor x^32 the register lacks; fetched now, used after the
@@ -242,6 +251,70 @@ __device__ __forceinline__ void tile_body(
     };
     auto whole_tile = [&](auto rows_c, auto depth_c, const uint8_t* bp, const uint8_t* tp) {
         whole_rows(rows_c, depth_c, bp, tp);
+        if (folding) store_register(reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]));
+    };
+    // Restore of a whole tile whose place in its tensor does not start on a 128-byte line.  Stored
+    // as loaded, every row would be a 1 KiB store that straddles line boundaries at both ends and
+    // in every 256-byte quarter.  Instead the rows pass through a two-row ring in LDS that belongs
+    // to this wavefront alone and leave it shifted by the misalignment m: output row R holds the
+    // tile's bytes [1024 R - m, 1024 R - m + 1024) and goes to a line-aligned address.  Rows 0 and
+    // kWholeRows of the output are partial (the first lacks its leading m bytes, the last holds
+    // only m) and are stored lane by lane, the lane on the edge halfword by halfword.  The fold
+    // takes the rows as loaded, so the CRC is untouched.  LDS operations of one wavefront complete
+    // in order, so a row written is visible to the reads that follow without a barrier.
+    auto whole_tile_realigned = [&](const uint8_t* bp, const uint64_t t0) {
+        constexpr int kRows = kWholeRows;
+        const uint32_t m = static_cast<uint32_t>(t0) & 127u;
+        uint8_t* const ap = reinterpret_cast<uint8_t*>(t0 - m) + lane16;  // lane's slot, output row 0
+        // ring: rows at byte 1024 * (row & 1); bytes [2048, 2064) repeat bytes [0, 16) so that a
+        // read that starts in the last 14 bytes runs on into the even row's beginning
+        const uint32_t o0 = (lane16 - m) & 2047u;  // lane's first byte, even output rows
+        const uint32_t o1 = (o0 + 1024u) & 2047u;  // odd output rows
+        const uint32_t sh = (m & 2u) * 8u;         // the lane's bytes start this far into a dword
+        const uint32_t* const r0 = ring + (o0 >> 2);
+        const uint32_t* const r1 = ring + (o1 >> 2);
+        auto take = [&](const uint32_t* r) {
+            uint32_t d[5];
+            static_for<5>([&](auto k) { d[k] = r[k]; });
+            return u32x4{__builtin_amdgcn_alignbit(d[1], d[0], sh), __builtin_amdgcn_alignbit(d[2], d[1], sh),
+                         __builtin_amdgcn_alignbit(d[3], d[2], sh), __builtin_amdgcn_alignbit(d[4], d[3], sh)};
+        };
+        // bytes [lo, hi) of an output row: whole slots as one store, the slot on an edge by halfwords
+        auto store_part = [&](uint8_t* p, const u32x4 y, const uint32_t lo, const uint32_t hi) {
+            if (lane16 >= lo && lane16 + 16u <= hi) {
+                store16_stream<kSegNT>(p, y);
+            } else if (lane16 + 16u > lo && lane16 < hi) {
+                const uint32_t d[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+                for (int u = 0; u < 8; u++) {
+                    const uint32_t pos = lane16 + 2u * u;
+                    if (pos >= lo && pos < hi)
+                        *as_global(reinterpret_cast<uint16_t*>(p + 2 * u)) =
+                            static_cast<uint16_t>(d[u >> 1] >> ((u & 1) * 16));
+                }
+            }
+        };
+        constexpr int kD = kRealignDepth;
+        u32x4 w[kD];
+        static_for<kD>([&](auto k) { w[k] = load16_stream<kBufNT>(bp + k * kRowBytes); });
+        static_for<kRows>([&](auto Jc) {
+            constexpr int J = Jc;
+            const u32x4 x = w[J % kD];
+            *reinterpret_cast<u32x4*>(ring + (J & 1) * 256 + 4 * lane) = x;
+            if ((J & 1) == 0 && lane == 0) *reinterpret_cast<u32x4*>(ring + 512) = x;
+            const u32x4 y = take((J & 1) ? r1 : r0);
+            fold_word<J % kNE>(S, x);
+            if constexpr (J + kD < kRows) {
+                __builtin_amdgcn_sched_barrier(0);
+                w[J % kD] = load16_stream<kBufNT>(bp + (J + kD) * kRowBytes);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (J == 0)
+                store_part(ap, y, m, kRowBytes);
+            else
+                store16_stream<kSegNT>(ap + J * kRowBytes, y);
+        });
+        store_part(ap + kRows * kRowBytes, take(r0), 0u, m);
         if (folding) store_register(reduce_state<Fold>(S, tab, tab_u_global[1024 + lane]));
     };
     // Pack: a default-size tile that the plan found inside one segment starts after a single
@@ -308,6 +381,13 @@ __device__ __forceinline__ void tile_body(
             bool whole = true;
             if (MODE == kRestore) whole = span_in_segment(cout, s_base, kWholeRows, &tp);
             if (whole) {
+                if (MODE == kRestore && ring) {
+                    const uint64_t t0 = cout.base + (s_base - cout.a);
+                    if (t0 & 127u) {
+                        whole_tile_realigned(bp, t0);
+                        return;
+                    }
+                }
                 whole_tile(std::integral_constant<int, kWholeRows>{},
                            std::integral_constant<int, kWholeDepth<MODE>>{}, bp, tp);
                 return;
@@ -337,45 +417,65 @@ __device__ __forceinline__ void tile_body(
         if (MODE != kVerify && T.tile_rows == kWholeRows && s_base < T.payload) {
             constexpr int kPieces = 4;
             const uint32_t first = tile_first_seg[tile];
-            uint64_t a[kPieces + 1];
-            static_for<kPieces + 1>([&](auto k) {
-                const uint32_t i = first + k < T.n_seg ? first + k : T.n_seg;
-                a[k] = seg_off[i];  // seg_off[n_seg] is the payload size
-            });
-            if (a[kPieces] >= s_base + uint64_t(kWholeRows) * kRowBytes || a[kPieces] >= T.payload) {
+            static_assert(kPieces == 4, "the selection chains below are written out");
+            // stream offsets of the first five segments from `first` on (seg_off[n_seg] is the
+            // payload size); plain scalars throughout, so that everything stays in registers
+            auto seg_begin = [&](uint32_t k) { return seg_off[first + k < T.n_seg ? first + k : T.n_seg]; };
+            const uint64_t a0 = seg_begin(0), a1 = seg_begin(1), a2 = seg_begin(2), a3 = seg_begin(3),
+                           a4 = seg_begin(4);
+            if (a4 >= s_base + uint64_t(kWholeRows) * kRowBytes || a4 >= T.payload) {
                 constexpr uint32_t kTileBytes = kWholeRows * kRowBytes;
                 const uint64_t left = T.payload - s_base;  // payload bytes from the tile start on
                 const uint32_t pend = left < kTileBytes ? static_cast<uint32_t>(left) : kTileBytes;
-                uint32_t rb[kPieces - 1];  // boundaries relative to the tile (>= kTileBytes: none)
-                uint64_t base[kPieces];    // address of tile offset 0 if it lay in segment k
-                static_for<kPieces>([&](auto k) {
-                    const uint32_t i = first + k < T.n_seg ? first + k : T.n_seg - 1;
-                    base[k] = seg_ptr[i] + (s_base - a[k]);  // modulo 2^64 for k >= 1
-                });
-                static_for<kPieces - 1>([&](auto k) {
-                    const uint64_t d = a[k + 1] - s_base;  // a[k + 1] > s_base
-                    rb[k] = d < kTileBytes ? static_cast<uint32_t>(d) : kTileBytes;
-                });
+                // per segment, the address tile offset 0 would have if it lay in that segment
+                // (modulo 2^64 for all but the first), and the boundaries relative to the tile
+                // (>= kTileBytes: none)
+                auto seg_base = [&](uint32_t k, uint64_t ak) {
+                    return seg_ptr[first + k < T.n_seg ? first + k : T.n_seg - 1] + (s_base - ak);
+                };
+                auto rel_bound = [&](uint64_t ak) {  // ak > s_base
+                    const uint64_t d = ak - s_base;
+                    return d < kTileBytes ? static_cast<uint32_t>(d) : kTileBytes;
+                };
+                const uint64_t base0 = seg_base(0, a0), base1 = seg_base(1, a1), base2 = seg_base(2, a2),
+                               base3 = seg_base(3, a3);
+                const uint32_t rb0 = rel_bound(a1), rb1 = rel_bound(a2), rb2 = rel_bound(a3);
+                // A lane's segment base is base0 plus the steps of the boundaries it lies behind.
+                // (Sums of `condition ? step : 0` on purpose: a chain of `condition ? base_k : b`
+                // over captured variables gets rewritten into a choice between their addresses
+                // followed by a load, which forces them all into memory.)
+                const uint64_t step1 = base1 - base0, step2 = base2 - base1, step3 = base3 - base2;
+                auto lane_base = [&](uint32_t rel) {
+                    return base0 + (rel >= rb0 ? step1 : 0) + (rel >= rb1 ? step2 : 0) +
+                           (rel >= rb2 ? step3 : 0);
+                };
                 // per-lane address of the lane's 16 bytes of row J on the tensor side, whether
                 // they straddle a boundary, and whether they lie wholly behind the payload
                 auto locate = [&](int J, bool& straddle, bool& beyond) -> const uint8_t* {
                     const uint32_t rel = static_cast<uint32_t>(J) * kRowBytes + lane16;
-                    uint64_t b = base[0];
                     beyond = rel >= pend;
-                    straddle = !beyond && rel + 16u > pend;
-                    static_for<kPieces - 1>([&](auto k) {
-                        const bool past = rel >= rb[k];
-                        b = past ? base[k + 1] : b;
-                        straddle = straddle || (!past && rel + 16u > rb[k]);
-                    });
-                    return reinterpret_cast<const uint8_t*>(b + rel);
+                    straddle = (!beyond && rel + 16u > pend) || (rel < rb0 && rel + 16u > rb0) ||
+                               (rel < rb1 && rel + 16u > rb1) || (rel < rb2 && rel + 16u > rb2);
+                    return reinterpret_cast<const uint8_t*>(lane_base(rel) + rel);
                 };
                 // address of the halfword at tile offset rel2 (a halfword never straddles)
-                auto locate_half = [&](uint32_t rel2) -> uint64_t {
-                    uint64_t b = base[0];
-                    static_for<kPieces - 1>([&](auto k) { b = rel2 >= rb[k] ? base[k + 1] : b; });
-                    return b + rel2;
-                };
+                auto locate_half = [&](uint32_t rel2) -> uint64_t { return lane_base(rel2) + rel2; };
+                // Pack: the (at most kPieces) 16-byte slots of the tile that straddle a boundary
+                // are fetched before anything else, halfword by halfword: lane 8k + u takes
+                // halfword u of the slot that holds boundary k (k = kPieces - 1: the end of the
+                // payload).  The owner of such a slot later collects its 8 halfwords from those
+                // lanes, so no row of the tile has to wait for loads issued in that row.
+                uint32_t fix = 0;
+                if (MODE == kPack) {
+                    const int k = lane >> 3, u = lane & 7;
+                    const uint32_t bnd = pend + (k == 0 ? rb0 - pend : 0) + (k == 1 ? rb1 - pend : 0) +
+                                         (k == 2 ? rb2 - pend : 0);
+                    if (k < kPieces && bnd < kTileBytes && (bnd & 15u)) {
+                        const uint32_t rel2 = (bnd & ~15u) + 2u * u;
+                        if (rel2 < pend)
+                            fix = *as_global(reinterpret_cast<const uint16_t*>(locate_half(rel2)));
+                    }
+                }
                 constexpr int kD = kWholeDepth<kPack>;
                 auto fetch = [&](int J) -> u32x4 {
                     if (MODE == kRestore) return load16_stream<kBufNT>(bp + J * kRowBytes);
@@ -394,18 +494,19 @@ __device__ __forceinline__ void tile_body(
                     const uint32_t rel = static_cast<uint32_t>(J) * kRowBytes + lane16;
                     if (MODE == kPack) {
                         if (beyond) x = u32x4{0, 0, 0, 0};
-                        if (straddle) {  // halfword by halfword, zeros behind the payload
-                            uint32_t h[8];
-#pragma unroll
-                            for (int u = 0; u < 8; u++) {
-                                const uint32_t rel2 = rel + 2u * u;
-                                h[u] = 0;
-                                if (rel2 < pend)
-                                    h[u] = *as_global(reinterpret_cast<const uint16_t*>(locate_half(rel2)));
+                        static_for<kPieces>([&](auto kk) {
+                            constexpr int k = kk;
+                            const uint32_t bnd = k == 0 ? rb0 : k == 1 ? rb1 : k == 2 ? rb2 : pend;
+                            if (bnd < kTileBytes && (bnd & 15u) && (bnd >> 10) == uint32_t(J)) {
+                                uint32_t h[8];
+                                static_for<8>([&](auto u) {
+                                    h[u] = __builtin_amdgcn_readlane(fix, 8 * k + u);
+                                });
+                                if (uint32_t(lane) == ((bnd & 1023u) >> 4))
+                                    x = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16),
+                                              h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
                             }
-                            x = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16),
-                                      h[6] | (h[7] << 16)};
-                        }
+                        });
                         store16_stream<kBufNT>(const_cast<uint8_t*>(bp) + J * kRowBytes, x);
                     } else {
                         if (straddle) {
@@ -422,8 +523,10 @@ __device__ __forceinline__ void tile_body(
                         }
                     }
                     fold_word<J % kNE>(S, x);
+                    // the fence also keeps the address arithmetic of later rows from being moved
+                    // up here, where it would only hold registers
+                    __builtin_amdgcn_sched_barrier(0);
                     if constexpr (J + kD < kWholeRows) {
-                        __builtin_amdgcn_sched_barrier(0);
                         w[J % kD] = fetch(J + kD);
                         __builtin_amdgcn_sched_barrier(0);
                     }
@@ -435,6 +538,7 @@ __device__ __forceinline__ void tile_body(
     }
 
     // queue slot of row r is (r + pad) mod kDepth; fill the first kDepth rows
+    constexpr int kDepth = kDepthOf<MODE>;
     u32x4 q[kDepth];
     {
         const uint8_t* lp = chunks + s_base + lane16;
@@ -530,13 +634,15 @@ __device__ __forceinline__ void tile_body(
 // slot div tiles per chunk.  The list travels in the kernel arguments, so a call needs no device
 // memory of its own for it.
 template <int MODE, int HINT>
-__global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
+__global__ __launch_bounds__(kWaveSize* kWavesPerBlock) __attribute__((amdgpu_waves_per_eu(2))) void
+tile_kernel(
     const uint64_t* __restrict__ seg_off, const uint64_t* __restrict__ seg_ptr,
     const uint32_t* __restrict__ tile_first_seg, const uint32_t* __restrict__ tab_u_global,
     uint32_t* __restrict__ partial, uint32_t* __restrict__ acc, uint8_t* __restrict__ chunks,
     TileTables T)
 {
     __shared__ uint32_t tab[1024];
+    __shared__ __align__(16) uint32_t ring[MODE == kRestore ? kWavesPerBlock : 1][kRingWords];
     for (int i = threadIdx.x; i < 1024; i += blockDim.x) tab[i] = tab_u_global[i];
     __syncthreads();
     const int lane = threadIdx.x & (kWaveSize - 1);
@@ -546,7 +652,7 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel(
     const uint32_t tile = T.tile_begin + slot;
     if (T.skip_bad && __builtin_amdgcn_readfirstlane(T.skip_bad[tile >> T.tpc_log2])) return;
     tile_body<MODE, HINT>(seg_off, seg_ptr, tile_first_seg, tab_u_global, partial, acc, chunks, T, tab,
-                          tile, lane);
+                          MODE == kRestore ? ring[wave] : nullptr, tile, lane);
 }
 
 template <int MODE>
@@ -566,7 +672,7 @@ __global__ __launch_bounds__(kWaveSize* kWavesPerBlock) void tile_kernel_listed(
     const uint32_t tile = (chunk << T.tpc_log2) + (slot & (T.tiles_per_chunk - 1));
     if (T.skip_bad && __builtin_amdgcn_readfirstlane(T.skip_bad[chunk])) return;
     tile_body<MODE, 3>(seg_off, seg_ptr, tile_first_seg, tab_u_global, nullptr, acc, chunks, T, tab,
-                       tile, lane);
+                       nullptr, tile, lane);
 }
 
 // ---- per-chunk kernels around the tiles ---------------------------------------------------------

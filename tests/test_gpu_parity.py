@@ -117,6 +117,18 @@ def test_tiles_with_a_few_segment_boundaries(oracle, seed):
     _restore_and_compare(shard, *state[:6])
 
 
+def test_whole_tiles_at_every_offset_within_a_line(oracle):
+    # tensors of 3-4 tiles each, ragged, starting at every even offset within a 128-byte line:
+    # most tiles lie inside one tensor, at every misalignment of the tensor side (on restore
+    # these are the tiles whose stores are lined up with the tensor)
+    rng = np.random.default_rng(5)
+    lay = [(int(rng.integers(48000, 60000)), 2, int(rng.integers(0, 8)) * 2) for _ in range(320)]
+    shard = wl.fragmented_shard(lay, 1 << 18, seed=5, device=DEV)
+    assert len({o % 128 for o, _ in shard.spans}) == 64
+    state = _pack_and_compare(shard, oracle)
+    _restore_and_compare(shard, *state[:6])
+
+
 @pytest.mark.parametrize("tail", [2, 14, 16, 18, 1022, 1024, 1026, 16384 + 6, 32766])
 def test_payload_end_inside_a_tile(oracle, tail):
     # three full tiles, then `tail` bytes split over segments of 2-byte granularity: the payload
