@@ -72,10 +72,11 @@ def parse():
                          "as large as the snapshot)")
     ap.add_argument("--tile-log2", type=int, default=0, help="tuning: log2 of the tile size")
     ap.add_argument("--workload", default="llama7b",
-                    choices=["llama7b", "llama70b", "fragmented", "tiny"],
-                    help="llama7b is the headline shard; the others are the remaining "
-                         "configurations, timed the same way (fused step where the shard has "
-                         "parameter groups and gradients)")
+                    help="llama7b is the headline shard; llama70b, fragmented and tiny are the "
+                         "remaining configurations, timed the same way (fused step where the "
+                         "shard has parameter groups and gradients); the names in "
+                         "workloads.LAYOUT_VARIANTS (fragmented-16, tensors-32k-gaps, ...) are "
+                         "variants of the fragmented shard that take its cost apart")
     return ap.parse_args()
 
 
@@ -234,8 +235,13 @@ def main():
         shard = wl.config_llama70b(dev)
     elif args.workload == "fragmented":
         shard = wl.config_fragmented(dev)
-    else:
+    elif args.workload in wl.LAYOUT_VARIANTS:
+        shard = wl.config_layout_variant(args.workload, dev)
+    elif args.workload == "tiny":
         shard = wl.config_tiny(dev)
+    else:
+        print("bench.py: unknown workload %r" % args.workload, file=sys.stderr)
+        sys.exit(2)
     plan = ff.plan_for_shard(shard, tile_log2=args.tile_log2)
     chunks, crcs, bad, n_bad = ff.alloc_outputs(plan, dev)
     N = plan.payload_bytes

@@ -164,6 +164,52 @@ def config_fragmented(device="cpu", n_tensors=20000, max_numel=4 * MiB):
     return fragmented_shard(lay, 4 * MiB, SEED_BASE + 3, device)
 
 
+# Variants of the fragmented configuration that take its cost apart: the same 20,000 sizes with
+# sizes and starts rounded to various grids, and uniform layouts that put every tile on one path
+# of the tile kernels.  name -> (what it is, layout builder, largest gap between tensors)
+def _rounded(grid, mis=lambda a: 0):
+    """The fragmented layout with every size in bytes rounded up to a multiple of `grid` (to the
+    nearest multiple, at least one, for the tile-sized grid) and the misalignment mapped by `mis`."""
+    def build():
+        out = []
+        for n, s, a in fragmented_layout(SEED_BASE + 3):
+            nbytes = n * s
+            if grid >= 1024:
+                nbytes = max(grid, (nbytes + grid // 2) // grid * grid)
+            else:
+                nbytes = (nbytes + grid - 1) // grid * grid
+            out.append((nbytes // s, s, mis(a)))
+        return out
+    return build
+
+
+LAYOUT_VARIANTS = {
+    "fragmented-tiles": ("sizes rounded to whole 32 KiB tiles, tensors back to back",
+                         _rounded(32768), 0),
+    "fragmented-16": ("sizes and starts rounded to 16 bytes", _rounded(16), 64),
+    "fragmented-16-off4": ("sizes rounded to 16 bytes, starts off by multiples of 4 bytes",
+                           _rounded(16, mis=lambda a: a // 4 * 4), 64),
+    "fragmented-16-off2": ("sizes rounded to 16 bytes, starts off by multiples of 2 bytes",
+                           _rounded(16, mis=lambda a: a), 64),
+    "tensors-32k": ("100,000 tensors of 32 KiB back to back", lambda: [(8192, 4, 0)] * 100000, 0),
+    "tensors-32k-gaps": ("100,000 tensors of 32 KiB, gaps of 0-64 bytes in steps of 16",
+                         lambda: [(8192, 4, 0)] * 100000, 64),
+    "tensors-33k": ("100,000 tensors of 33 KiB: every tile touches two tensors",
+                    lambda: [(33 * 256, 4, 0)] * 100000, 64),
+    "tensors-11k": ("300,000 tensors of 11 KiB: every tile touches 3-4 tensors",
+                    lambda: [(11 * 256, 4, 0)] * 300000, 64),
+    "tensors-5k": ("200,000 tensors of 5 KiB: every tile on the general path",
+                   lambda: [(5 * 256, 4, 0)] * 200000, 64),
+    "tensors-5k-ragged": ("200,000 bf16 tensors of 5 KiB + 2 bytes: general path, every boundary "
+                          "inside a lane's 16 bytes", lambda: [(5 * 512 + 1, 2, 0)] * 200000, 64),
+}
+
+
+def config_layout_variant(name, device="cpu"):
+    _, build, max_gap = LAYOUT_VARIANTS[name]
+    return fragmented_shard(build(), 4 * MiB, SEED_BASE + 3, device, name=name, max_gap=max_gap)
+
+
 def config_llama70b(device):
     return param_shard("llama70b-dp64", llama70b_dp64_numels(), 8 * MiB, SEED_BASE + 5, device)
 
