@@ -93,15 +93,21 @@ __device__ __forceinline__ void cursor_seek(Cursor& c, const uint64_t* __restric
 }
 
 // Per-lane: index of the segment holding stream offset pos, searching upwards from si0, the
-// segment that holds the start of the lane's row (pos is less than 1 KiB past it and every
-// segment has at least 2 bytes, so the answer is within 512 segments).
+// segment that holds the start of the lane's row.  The answer is nearly always si0 or its
+// successor, so the search gallops (steps of 1, 2, 4, ...) until it has passed pos and then
+// bisects the last step: one table read when the answer is si0, three when it is si0 + 1.
 __device__ __forceinline__ uint32_t find_segment(const uint64_t* __restrict__ seg_off,
                                                  uint32_t n_seg, uint32_t si0, uint64_t pos)
 {
-    uint32_t lo = si0;
-    uint32_t hi = (n_seg - 1 - si0 > 512u) ? si0 + 512u : n_seg - 1;
+    uint32_t lo = si0, step = 1;
+    while (lo + step < n_seg && seg_off[lo + step] <= pos) {
+        lo += step;
+        step <<= 1;
+    }
+    // seg_off[lo] <= pos, and seg_off[lo + step] > pos or lo + step is past the last segment
+    uint32_t hi = (lo + step < n_seg) ? lo + step - 1 : n_seg - 1;
     while (lo < hi) {
-        uint32_t mid = lo + (hi - lo + 1) / 2;
+        const uint32_t mid = lo + (hi - lo + 1) / 2;
         if (seg_off[mid] <= pos)
             lo = mid;
         else
