@@ -46,10 +46,11 @@ constexpr int kWholeRows = 32;   // rows of a default (32 KiB) tile
 constexpr int kRealignDepth = 16;  // rows in flight on the restore path that re-aligns its stores
 constexpr int kRingWords = 520;  // two rows and 16 bytes, as dwords, padded to a multiple of 16 bytes
 constexpr int kVerifyRows = 64;  // a read-only pass walks its grouped tile in blocks of 64 rows
-// rows requested before the first store on that path (measured: 16 is best when the stores go to
-// the chunk buffer, the whole tile when they go to the tensors)
+// rows requested before the first store on that path (measured on the 7B and 70B/64 shards: with
+// the stores going to the chunk buffer 26-30 rows are best, 1 % ahead of 16 and of the whole
+// tile; with the stores going to the tensors the whole tile is; a read-only pass keeps 16)
 template <int MODE>
-constexpr int kWholeDepth = (MODE == kRestore) ? 32 : 16;
+constexpr int kWholeDepth = (MODE == kRestore) ? 32 : (MODE == kPack) ? 28 : 16;
 static_assert(kNE % kDepthOf<kPack> == 0 && kNE % kDepthOf<kRestore> == 0,
               "queue slots must repeat with the state rotation");
 static_assert(kNF == 4 && kRowBytes == 1024, "one 16-byte word per lane per row");
@@ -482,7 +483,9 @@ __device__ __forceinline__ void tile_body(
                             fix = *as_global(reinterpret_cast<const uint16_t*>(locate_half(rel2)));
                     }
                 }
-                constexpr int kD = kWholeDepth<kPack>;
+                // rows in flight: pack as on its whole-tile path; restore, whose stores here go to
+                // per-lane addresses, does best with 16 (28: 3 % slower on tiles of two tensors)
+                constexpr int kD = (MODE == kPack) ? kWholeDepth<kPack> : 16;
                 auto fetch = [&](int J) -> u32x4 {
                     if (MODE == kRestore) return load16_stream<kBufNT>(bp + J * kRowBytes);
                     bool straddle, beyond;
